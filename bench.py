@@ -1,0 +1,169 @@
+#!/usr/bin/env python3
+"""Benchmark of the radial-attention hot path on one MI355X.
+
+A step = the radial mask build + one block-sparse attention forward over the whole
+[B, H, N, D] workload (plus the backward for the forward+backward workload).  Inputs are
+synthetic and resident in HBM before the timed region.  Prints one JSON line: effective
+TFLOP/s on computed blocks, the kernel's fraction of the bf16 MFMA peak, the dense baseline
+(same kernel, all-ones list) and the CPU oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+
+
+def effective_flops(row_ptr, col_idx, n_tokens, block, D, heads):
+    """4*D*sum over listed pairs of rows(qb)*cols(kb): both products, real tokens only."""
+    import numpy as np
+    nb = row_ptr.size - 1
+    size = np.full(nb, block, dtype=np.int64)
+    size[-1] = n_tokens - (nb - 1) * block
+    rows = np.repeat(size, np.diff(row_ptr).astype(np.int64))
+    pairs = int((rows * size[col_idx]).sum())
+    return 4 * D * pairs * heads
+
+
+def cpu_baseline(w, x, row_ptr, col_idx, budget_s=12.0):
+    """Times the CPU oracle (float64 numpy, as it stands) on query blocks of head 0 until the
+    time budget is used; reports TFLOP/s with the same flop count as the GPU metric."""
+    import numpy as np
+    from oracle import attention as oa
+    q, k, v = (x[n][0, 0].float().cpu().numpy() for n in ("q", "k", "v"))
+    nb = row_ptr.size - 1
+    picks = np.random.default_rng(w.seed).permutation(nb)
+    done, flops, t0 = 0, 0, time.perf_counter()
+    for qb in picks:
+        cols = col_idx[row_ptr[qb]:row_ptr[qb + 1]]
+        keys = (cols[:, None].astype(np.int64) * w.block + np.arange(w.block)[None, :]).ravel()
+        keys = keys[keys < w.N]
+        rows = np.arange(qb * w.block, min(w.N, (qb + 1) * w.block))
+        oa.attention_rows_keyset(q[rows], k, v, keys, w.scale)
+        flops += 4 * w.D * rows.size * keys.size
+        done += 1
+        if time.perf_counter() - t0 > budget_s:
+            break
+    dt = time.perf_counter() - t0
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{done} of {nb} query blocks of head 0 ({w.name}), float64 numpy, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg3_hunyuan720p")
+    ap.add_argument("--dense-steps", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2506_19852_amd import binding as rb
+    from paper_2506_19852_amd import workloads as wl
+
+    w = wl.WORKLOADS[args.workload]
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    x = wl.make_inputs(w, dev)
+    flags = rb.RADIAL_MASK_TRANSPOSE if w.backward else 0
+    out = torch.empty_like(x["q"])
+    lse = torch.empty((w.B, w.H, w.N), dtype=torch.float32, device=dev)
+    grads = ws = None
+    if w.backward:
+        grads = [torch.empty_like(x["q"]) for _ in range(3)]
+
+    def step(keep=None):
+        m = rb.radial_mask_build(w.frames, w.tokens_per_frame, w.block, 1, flags)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        rb.radial_attn_fwd(x["q"], x["k"], x["v"], out, lse, m, w.scale)
+        e1.record()
+        if w.backward:
+            nonlocal ws
+            if ws is None:
+                ws = torch.empty(rb.radial_attn_bwd_workspace(w.B, w.H, w.N, w.D, m), dtype=torch.uint8, device=dev)
+            rb.radial_attn_bwd(x["q"], x["k"], x["v"], out, x["do"], lse, *grads, m, w.scale, ws)
+        if keep is not None:
+            keep.append((m, e0, e1))
+        else:
+            torch.cuda.synchronize()
+            m.free()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    keep = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(keep)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    kernel_ms = float(np.mean([e0.elapsed_time(e1) for (_, e0, e1) in keep]))
+    row_ptr, col_idx = rb.radial_mask_copy_to_host(keep[0][0])
+    for m, _, _ in keep:
+        m.free()
+
+    fwd_flops = effective_flops(row_ptr, col_idx, w.N, w.block, w.D, w.B * w.H)
+    step_flops = fwd_flops * (3.5 if w.backward else 1.0)      # backward = 5 products vs 2
+    ms_per_step = dt / args.steps * 1e3
+    value = step_flops / (dt / args.steps) / 1e12
+
+    # dense baseline: same kernel, all-ones list
+    dense = rb.radial_mask_build_dense(w.N, w.block)
+    dptr, didx = rb.radial_mask_copy_to_host(dense)
+    dense_flops = effective_flops(dptr, didx, w.N, w.block, w.D, w.B * w.H)
+    rb.radial_attn_fwd(x["q"], x["k"], x["v"], out, None, dense, w.scale)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.dense_steps):
+        rb.radial_attn_fwd(x["q"], x["k"], x["v"], out, None, dense, w.scale)
+    e1.record()
+    torch.cuda.synchronize()
+    dense_ms = e0.elapsed_time(e1) / args.dense_steps
+    dense.free()
+
+    achieved = fwd_flops / (kernel_ms * 1e-3) / 1e12
+    result = {
+        "metric": "effective TFLOP/s on computed blocks + speedup vs dense attn at same N, 1 GPU",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "D": w.D, "frames": w.frames,
+                   "tokens_per_frame": w.tokens_per_frame, "block": w.block, "sink_frames": 1,
+                   "listed_block_pairs": int(row_ptr[-1]), "pass": "fwd+bwd" if w.backward else "fwd"},
+        "fwd_kernel_ms": round(kernel_ms, 3),
+        "dense_fwd_kernel_ms": round(dense_ms, 3),
+        "dense_tflops": round(dense_flops / (dense_ms * 1e-3) / 1e12, 2),
+        "speedup_vs_dense": round(dense_ms / kernel_ms, 3),
+        "block_ratio_dense_over_radial": round(dense_flops / fwd_flops, 3),
+        "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                     "kernel": "radial_fwd_kernel", "flops_per_launch": fwd_flops},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, x, row_ptr, col_idx)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

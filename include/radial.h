@@ -29,6 +29,12 @@
 extern "C" {
 #endif
 
+#if defined(__GNUC__)
+#define RADIAL_API __attribute__((visibility("default")))
+#else
+#define RADIAL_API
+#endif
+
 typedef enum {
   RADIAL_OK = 0,
   RADIAL_EINVAL = -1,       /* NULL where a pointer is required, bad parameter value, unsorted list   */
@@ -38,7 +44,7 @@ typedef enum {
   RADIAL_ESHAPE = -5        /* tensor shape / stride / workspace does not match the mask or the call */
 } radial_status;
 
-const char* radial_last_error(void);
+RADIAL_API const char* radial_last_error(void);
 
 /* ---- mask ------------------------------------------------------------------------------- */
 
@@ -70,34 +76,34 @@ typedef struct radial_mask radial_mask;
 /* Builds the radial block lists with integer kernels on the GPU.  *out receives a new mask
  * that the caller releases with radial_mask_free.  Errors: EINVAL (NULL, f<1, s<1, sink<0,
  * unknown flag, N too large), EUNSUPPORTED (block), ENOMEM, EHIP. */
-int radial_mask_build(const radial_mask_params* params, void* hip_stream, radial_mask** out);
+RADIAL_API int radial_mask_build(const radial_mask_params* params, void* hip_stream, radial_mask** out);
 
 /* The all-ones list over ceil(n_tokens/block)^2 block pairs: dense attention, Eq. 1.
  * `flags` as in radial_mask_params. */
-int radial_mask_build_dense(int32_t n_tokens, int32_t block, uint32_t flags, void* hip_stream,
+RADIAL_API int radial_mask_build_dense(int32_t n_tokens, int32_t block, uint32_t flags, void* hip_stream,
                             radial_mask** out);
 
 /* A caller-supplied list.  row_ptr [nqb+1] and col_idx [row_ptr[nqb]] are HOST pointers,
  * copied.  Each row must be strictly ascending with entries in [0, nqb); row_ptr[0] == 0 and
  * non-decreasing (else EINVAL).  Rows may be empty. */
-int radial_mask_from_csr(int32_t n_tokens, int32_t block, uint32_t flags, const int32_t* row_ptr,
+RADIAL_API int radial_mask_from_csr(int32_t n_tokens, int32_t block, uint32_t flags, const int32_t* row_ptr,
                          const int32_t* col_idx, void* hip_stream, radial_mask** out);
 
 /* Any out-pointer may be NULL.  n_blocks = ceil(n_tokens/block); nnz = listed block pairs. */
-int radial_mask_info(const radial_mask* mask, int32_t* n_tokens, int32_t* block, int32_t* n_blocks,
+RADIAL_API int radial_mask_info(const radial_mask* mask, int32_t* n_tokens, int32_t* block, int32_t* n_blocks,
                      int64_t* nnz, uint32_t* flags);
 
 /* Copies the lists to HOST arrays row_ptr [n_blocks+1], col_idx [nnz] (either may be NULL).
  * Entries of a row ascend. */
-int radial_mask_copy_to_host(const radial_mask* mask, int32_t* row_ptr, int32_t* col_idx);
+RADIAL_API int radial_mask_copy_to_host(const radial_mask* mask, int32_t* row_ptr, int32_t* col_idx);
 
 /* Same for the transposed lists (col_ptr [n_blocks+1], row_idx [nnz]): for each key block the
  * ascending query blocks that list it.  ESHAPE if the mask was built without
  * RADIAL_MASK_TRANSPOSE. */
-int radial_mask_copy_transpose_to_host(const radial_mask* mask, int32_t* col_ptr, int32_t* row_idx);
+RADIAL_API int radial_mask_copy_transpose_to_host(const radial_mask* mask, int32_t* col_ptr, int32_t* row_idx);
 
 /* NULL-safe.  Must not be called while an attention call that uses the mask is in flight. */
-void radial_mask_free(radial_mask* mask);
+RADIAL_API void radial_mask_free(radial_mask* mask);
 
 /* ---- attention ---------------------------------------------------------------------------- */
 
@@ -121,12 +127,12 @@ typedef struct {
  * nearest-even bf16.  Allocates nothing.
  * Errors: EINVAL (NULL, scale), EUNSUPPORTED (D not 64/128), ESHAPE (N != mask n_tokens,
  * misaligned pointer/stride, B*H*n_blocks >= 2^31), EHIP. */
-int radial_attn_fwd(int32_t B, int32_t H, int32_t N, int32_t D, radial_tensor q, radial_tensor k,
+RADIAL_API int radial_attn_fwd(int32_t B, int32_t H, int32_t N, int32_t D, radial_tensor q, radial_tensor k,
                     radial_tensor v, radial_tensor out, float* lse, const radial_mask* mask,
                     float scale, void* hip_stream);
 
 /* Bytes of device workspace radial_attn_bwd needs for this problem (0 on invalid arguments). */
-size_t radial_attn_bwd_workspace(int32_t B, int32_t H, int32_t N, int32_t D, const radial_mask* mask);
+RADIAL_API size_t radial_attn_bwd_workspace(int32_t B, int32_t H, int32_t N, int32_t D, const radial_mask* mask);
 
 /* Backward of Eq. 2 for the scalar loss whose gradient w.r.t. `out` is `dout`:
  *   P = exp(scale*Q K^T - lse) on listed blocks,  dV = P^T dO,  dP = dO V^T,
@@ -136,7 +142,7 @@ size_t radial_attn_bwd_workspace(int32_t B, int32_t H, int32_t N, int32_t D, con
  *   workspace : device memory of at least radial_attn_bwd_workspace(...) bytes, 256-byte
  *               aligned, contents ignored on entry and undefined on return.
  * The mask must carry RADIAL_MASK_TRANSPOSE (ESHAPE otherwise).  Allocates nothing. */
-int radial_attn_bwd(int32_t B, int32_t H, int32_t N, int32_t D, radial_tensor q, radial_tensor k,
+RADIAL_API int radial_attn_bwd(int32_t B, int32_t H, int32_t N, int32_t D, radial_tensor q, radial_tensor k,
                     radial_tensor v, radial_tensor out, radial_tensor dout, const float* lse,
                     radial_tensor dq, radial_tensor dk, radial_tensor dv, const radial_mask* mask,
                     float scale, void* workspace, size_t workspace_bytes, void* hip_stream);

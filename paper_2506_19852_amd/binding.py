@@ -1,0 +1,201 @@
+"""ctypes binding of libradial.so: same names as the C ABI in include/radial.h, argument
+marshalling only.  Tensors are torch CUDA tensors (device memory + strides); every step of
+the computation runs in the library's HIP kernels.  There is no fallback: a missing library
+or a failing call raises."""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import POINTER, byref, c_float, c_int32, c_int64, c_size_t, c_uint32, c_void_p
+
+import numpy as np
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libradial.so")
+
+RADIAL_MASK_TRANSPOSE = 1
+STATUS = {0: "RADIAL_OK", -1: "RADIAL_EINVAL", -2: "RADIAL_ENOMEM", -3: "RADIAL_EHIP",
+          -4: "RADIAL_EUNSUPPORTED", -5: "RADIAL_ESHAPE"}
+
+EXPORTS = (
+    "radial_last_error", "radial_mask_build", "radial_mask_build_dense", "radial_mask_from_csr",
+    "radial_mask_info", "radial_mask_copy_to_host", "radial_mask_copy_transpose_to_host",
+    "radial_mask_free", "radial_attn_fwd", "radial_attn_bwd_workspace", "radial_attn_bwd",
+)
+
+
+class RadialError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"{STATUS.get(code, code)}: {message}")
+        self.code = code
+
+
+class radial_mask_params(ctypes.Structure):
+    _fields_ = [("frames", c_int32), ("tokens_per_frame", c_int32), ("block", c_int32),
+                ("sink_frames", c_int32), ("flags", c_uint32)]
+
+
+class radial_tensor(ctypes.Structure):
+    _fields_ = [("ptr", c_void_p), ("stride_b", c_int64), ("stride_h", c_int64), ("stride_n", c_int64)]
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load():
+    """Loads libradial.so (built by paper_2506_19852_amd.build) and declares the prototypes."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: run `python -m paper_2506_19852_amd.build` (needs hipcc)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    lib.radial_last_error.restype = ctypes.c_char_p
+    lib.radial_last_error.argtypes = []
+    lib.radial_mask_build.argtypes = [POINTER(radial_mask_params), c_void_p, POINTER(c_void_p)]
+    lib.radial_mask_build_dense.argtypes = [c_int32, c_int32, c_uint32, c_void_p, POINTER(c_void_p)]
+    lib.radial_mask_from_csr.argtypes = [c_int32, c_int32, c_uint32, c_void_p, c_void_p, c_void_p, POINTER(c_void_p)]
+    lib.radial_mask_info.argtypes = [c_void_p, POINTER(c_int32), POINTER(c_int32), POINTER(c_int32),
+                                     POINTER(c_int64), POINTER(c_uint32)]
+    lib.radial_mask_copy_to_host.argtypes = [c_void_p, c_void_p, c_void_p]
+    lib.radial_mask_copy_transpose_to_host.argtypes = [c_void_p, c_void_p, c_void_p]
+    lib.radial_mask_free.argtypes = [c_void_p]
+    lib.radial_mask_free.restype = None
+    lib.radial_attn_fwd.argtypes = [c_int32, c_int32, c_int32, c_int32, radial_tensor, radial_tensor, radial_tensor,
+                                    radial_tensor, c_void_p, c_void_p, c_float, c_void_p]
+    lib.radial_attn_bwd_workspace.argtypes = [c_int32, c_int32, c_int32, c_int32, c_void_p]
+    lib.radial_attn_bwd_workspace.restype = c_size_t
+    lib.radial_attn_bwd.argtypes = [c_int32, c_int32, c_int32, c_int32] + [radial_tensor] * 5 + [c_void_p] + \
+        [radial_tensor] * 3 + [c_void_p, c_float, c_void_p, c_size_t, c_void_p]
+    for name in EXPORTS:
+        fn = getattr(lib, name)
+        if name not in ("radial_last_error", "radial_mask_free", "radial_attn_bwd_workspace"):
+            fn.restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def radial_last_error() -> str:
+    return load().radial_last_error().decode()
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise RadialError(rc, radial_last_error())
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return c_void_p(int(getattr(stream, "cuda_stream", stream)))
+
+
+class RadialMask:
+    """Owner of a radial_mask* handle."""
+
+    def __init__(self, handle):
+        self._h = handle
+
+    @property
+    def handle(self):
+        if not self._h:
+            raise ValueError("mask was freed")
+        return self._h
+
+    def free(self):
+        if self._h:
+            load().radial_mask_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def radial_mask_build(frames: int, tokens_per_frame: int, block: int, sink_frames: int = 1, flags: int = 0,
+                      stream=None) -> RadialMask:
+    p = radial_mask_params(frames, tokens_per_frame, block, sink_frames, flags)
+    out = c_void_p()
+    _check(load().radial_mask_build(byref(p), _stream_ptr(stream), byref(out)))
+    return RadialMask(out)
+
+
+def radial_mask_build_dense(n_tokens: int, block: int, flags: int = 0, stream=None) -> RadialMask:
+    out = c_void_p()
+    _check(load().radial_mask_build_dense(n_tokens, block, flags, _stream_ptr(stream), byref(out)))
+    return RadialMask(out)
+
+
+def radial_mask_from_csr(n_tokens: int, block: int, row_ptr, col_idx, flags: int = 0, stream=None) -> RadialMask:
+    rp = np.ascontiguousarray(row_ptr, dtype=np.int32)
+    ci = np.ascontiguousarray(col_idx, dtype=np.int32)
+    out = c_void_p()
+    _check(load().radial_mask_from_csr(n_tokens, block, flags, rp.ctypes.data, ci.ctypes.data if ci.size else None,
+                                       _stream_ptr(stream), byref(out)))
+    return RadialMask(out)
+
+
+def radial_mask_info(mask: RadialMask) -> dict:
+    n, blk, nb, nnz, fl = c_int32(), c_int32(), c_int32(), c_int64(), c_uint32()
+    _check(load().radial_mask_info(mask.handle, byref(n), byref(blk), byref(nb), byref(nnz), byref(fl)))
+    return {"n_tokens": n.value, "block": blk.value, "n_blocks": nb.value, "nnz": nnz.value, "flags": fl.value}
+
+
+def radial_mask_copy_to_host(mask: RadialMask):
+    info = radial_mask_info(mask)
+    row_ptr = np.empty(info["n_blocks"] + 1, dtype=np.int32)
+    col_idx = np.empty(info["nnz"], dtype=np.int32)
+    _check(load().radial_mask_copy_to_host(mask.handle, row_ptr.ctypes.data, col_idx.ctypes.data if col_idx.size else None))
+    return row_ptr, col_idx
+
+
+def radial_mask_copy_transpose_to_host(mask: RadialMask):
+    info = radial_mask_info(mask)
+    col_ptr = np.empty(info["n_blocks"] + 1, dtype=np.int32)
+    row_idx = np.empty(info["nnz"], dtype=np.int32)
+    _check(load().radial_mask_copy_transpose_to_host(mask.handle, col_ptr.ctypes.data,
+                                                     row_idx.ctypes.data if row_idx.size else None))
+    return col_ptr, row_idx
+
+
+def _tensor(t, name) -> radial_tensor:
+    import torch
+    if t.dtype != torch.bfloat16 or not t.is_cuda or t.dim() != 4 or t.stride(3) != 1:
+        raise ValueError(f"{name} must be a CUDA bf16 tensor [B, H, N, D] with unit stride in D")
+    return radial_tensor(t.data_ptr(), t.stride(0), t.stride(1), t.stride(2))
+
+
+def radial_attn_fwd(q, k, v, out, lse, mask: RadialMask, scale: float, stream=None):
+    """out[B,H,N,D] (bf16) and lse[B,H,N] (fp32, or None) <- block-sparse attention of q, k, v."""
+    import torch
+    B, H, N, D = q.shape
+    for t, nm in ((k, "k"), (v, "v"), (out, "out")):
+        if tuple(t.shape) != (B, H, N, D):
+            raise ValueError(f"{nm} has shape {tuple(t.shape)}, expected {(B, H, N, D)}")
+    lse_ptr = None
+    if lse is not None:
+        if lse.dtype != torch.float32 or not lse.is_cuda or not lse.is_contiguous() or tuple(lse.shape) != (B, H, N):
+            raise ValueError("lse must be a contiguous CUDA float32 tensor [B, H, N]")
+        lse_ptr = c_void_p(lse.data_ptr())
+    _check(load().radial_attn_fwd(B, H, N, D, _tensor(q, "q"), _tensor(k, "k"), _tensor(v, "v"), _tensor(out, "out"),
+                                  lse_ptr, mask.handle, c_float(scale), _stream_ptr(stream)))
+
+
+def radial_attn_bwd_workspace(B: int, H: int, N: int, D: int, mask: RadialMask) -> int:
+    return int(load().radial_attn_bwd_workspace(B, H, N, D, mask.handle))
+
+
+def radial_attn_bwd(q, k, v, out, dout, lse, dq, dk, dv, mask: RadialMask, scale: float, workspace, stream=None):
+    """dq, dk, dv <- gradient of the block-sparse attention; workspace: CUDA uint8 tensor."""
+    B, H, N, D = q.shape
+    ts = [_tensor(t, nm) for t, nm in ((q, "q"), (k, "k"), (v, "v"), (out, "out"), (dout, "dout"))]
+    gs = [_tensor(t, nm) for t, nm in ((dq, "dq"), (dk, "dk"), (dv, "dv"))]
+    _check(load().radial_attn_bwd(B, H, N, D, *ts, c_void_p(lse.data_ptr()), *gs, mask.handle, c_float(scale),
+                                  c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
+                                  _stream_ptr(stream)))

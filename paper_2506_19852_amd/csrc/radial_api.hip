@@ -1,0 +1,91 @@
+// C-ABI entry points of the attention calls: argument checks, then the kernel launchers.
+#include <math.h>
+
+#include "radial_internal.h"
+
+using namespace radial;
+
+namespace {
+
+int check_tensor(const char* name, const radial_tensor& t, int32_t D) {
+  if (!t.ptr) return fail(RADIAL_EINVAL, "%s.ptr is NULL", name);
+  if (((uintptr_t)t.ptr & 15u) != 0) return fail(RADIAL_ESHAPE, "%s.ptr is not 16-byte aligned", name);
+  if (t.stride_n < D || (t.stride_n & 7) || (t.stride_h & 7) || (t.stride_b & 7) || t.stride_h < 0 || t.stride_b < 0)
+    return fail(RADIAL_ESHAPE, "%s strides must be non-negative multiples of 8 elements with stride_n >= D", name);
+  return RADIAL_OK;
+}
+
+int check_call(int32_t B, int32_t H, int32_t N, int32_t D, const radial_mask* mask, float scale) {
+  if (!mask) return fail(RADIAL_EINVAL, "mask is NULL");
+  if (B < 1 || H < 1 || N < 1) return fail(RADIAL_EINVAL, "B, H, N must be >= 1");
+  if (D != 64 && D != 128) return fail(RADIAL_EUNSUPPORTED, "head dimension must be 64 or 128 (got %d)", D);
+  if (N != mask->n_tokens) return fail(RADIAL_ESHAPE, "N = %d but the mask was built for %d tokens", N, mask->n_tokens);
+  if (!(scale > 0.f) || !isfinite(scale)) return fail(RADIAL_EINVAL, "scale must be positive and finite");
+  if ((int64_t)B * H * mask->n_blocks >= 0x7fffffffLL - 8) return fail(RADIAL_ESHAPE, "B*H*n_blocks does not fit one launch");
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev != mask->device)
+    return fail(RADIAL_ESHAPE, "mask lives on device %d, current device is %d", mask->device, dev);
+  return RADIAL_OK;
+}
+
+TensorArg arg(const radial_tensor& t) { return TensorArg{t.ptr, t.stride_b, t.stride_h, t.stride_n}; }
+
+}  // namespace
+
+extern "C" int radial_attn_fwd(int32_t B, int32_t H, int32_t N, int32_t D, radial_tensor q, radial_tensor k,
+                               radial_tensor v, radial_tensor out, float* lse, const radial_mask* mask, float scale,
+                               void* hip_stream) {
+  if (int rc = check_call(B, H, N, D, mask, scale)) return rc;
+  if (int rc = check_tensor("q", q, D)) return rc;
+  if (int rc = check_tensor("k", k, D)) return rc;
+  if (int rc = check_tensor("v", v, D)) return rc;
+  if (int rc = check_tensor("out", out, D)) return rc;
+  FwdArgs a;
+  a.q = arg(q); a.k = arg(k); a.v = arg(v); a.o = arg(out);
+  a.lse = lse;
+  a.row_ptr = mask->d_row_ptr;
+  a.col_idx = mask->d_col_idx;
+  a.order = mask->d_order;
+  a.B = B; a.H = H; a.N = N; a.n_blocks = mask->n_blocks;
+  a.scale = scale;
+  return launch_fwd(D, mask->block, a, (hipStream_t)hip_stream);
+}
+
+// Workspace layout: delta [B*H*N] fp32, then (256-byte aligned) dQ accumulator [B*H*N*D] fp32.
+static size_t delta_bytes(int32_t B, int32_t H, int32_t N) {
+  const size_t raw = (size_t)B * H * N * sizeof(float);
+  return (raw + 255) & ~(size_t)255;
+}
+
+extern "C" size_t radial_attn_bwd_workspace(int32_t B, int32_t H, int32_t N, int32_t D, const radial_mask* mask) {
+  if (!mask || B < 1 || H < 1 || N < 1 || (D != 64 && D != 128) || N != mask->n_tokens) return 0;
+  return delta_bytes(B, H, N) + (size_t)B * H * N * D * sizeof(float);
+}
+
+extern "C" int radial_attn_bwd(int32_t B, int32_t H, int32_t N, int32_t D, radial_tensor q, radial_tensor k,
+                               radial_tensor v, radial_tensor out, radial_tensor dout, const float* lse,
+                               radial_tensor dq, radial_tensor dk, radial_tensor dv, const radial_mask* mask,
+                               float scale, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (int rc = check_call(B, H, N, D, mask, scale)) return rc;
+  if (!(mask->flags & RADIAL_MASK_TRANSPOSE)) return fail(RADIAL_ESHAPE, "mask was built without RADIAL_MASK_TRANSPOSE");
+  if (!lse) return fail(RADIAL_EINVAL, "lse is NULL");
+  const radial_tensor* ts[] = {&q, &k, &v, &out, &dout, &dq, &dk, &dv};
+  const char* names[] = {"q", "k", "v", "out", "dout", "dq", "dk", "dv"};
+  for (int i = 0; i < 8; ++i)
+    if (int rc = check_tensor(names[i], *ts[i], D)) return rc;
+  const size_t need = radial_attn_bwd_workspace(B, H, N, D, mask);
+  if (!workspace || ((uintptr_t)workspace & 255u)) return fail(RADIAL_ESHAPE, "workspace must be a 256-byte aligned device pointer");
+  if (workspace_bytes < need) return fail(RADIAL_ESHAPE, "workspace holds %zu bytes, %zu needed", workspace_bytes, need);
+  BwdArgs a;
+  a.q = arg(q); a.k = arg(k); a.v = arg(v); a.o = arg(out); a.dout = arg(dout);
+  a.dq = arg(dq); a.dk = arg(dk); a.dv = arg(dv);
+  a.lse = lse;
+  a.delta = (float*)workspace;
+  a.dq_acc = (float*)((char*)workspace + delta_bytes(B, H, N));
+  a.row_ptr = mask->d_row_ptr; a.col_idx = mask->d_col_idx;
+  a.col_ptr = mask->d_col_ptr; a.row_idx = mask->d_row_idx;
+  a.order = mask->d_order; a.order_t = mask->d_order_t;
+  a.B = B; a.H = H; a.N = N; a.n_blocks = mask->n_blocks;
+  a.scale = scale;
+  return launch_bwd(D, mask->block, a, (hipStream_t)hip_stream);
+}

@@ -1,0 +1,325 @@
+// Block-sparse attention forward for gfx950: Eq. 2 of the paper evaluated only on the key
+// blocks that the block list names (Eq. 1 when the list names all of them).
+//
+// One workgroup = one (batch, head, query block).  Wave w owns 32 query rows.  Everything
+// that belongs to query row r lives in lanes r and r+32 of that wave, because both products
+// are computed transposed on v_mfma_f32_32x32x16_bf16:
+//     S^T[key, q] = K[key, :] . Q[q, :]      A = K tile (LDS),     B = Q^T (registers)
+//     O^T[d,   q] = V^T[d, key] . P^T[key, q] A = V^T (LDS, transposing read), B = P^T (registers)
+// The accumulator layout of the first product (column = lane%32, 16 rows per lane) is, 8
+// rows at a time, exactly the B-operand layout of the second one, so P never leaves
+// registers, row maxima and sums are in-lane reductions plus one exchange with lane^32, and
+// the running rescale of O is a per-lane multiply.
+//
+// Key blocks are walked in stages of 64 keys.  The K and V rows of a stage are copied
+// HBM -> LDS by global_load_lds (no register staging) into one of two LDS stage buffers; the
+// copy of stage u+1 is issued right after the barrier that opens stage u, so it overlaps
+// the whole of stage u's arithmetic and a stage needs exactly one barrier.  The copies are
+// issued from inline assembly and waited for explicitly (s_waitcnt vmcnt(0) before that
+// barrier): otherwise the compiler orders every LDS read after all outstanding copies.
+// 16-byte pieces are XOR-swizzled inside 256-byte LDS lines so that the 128-bit K reads and
+// the 64-bit transposing V reads are bank-conflict free.
+#include "radial_internal.h"
+
+namespace radial {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+// Generic pointer into a __shared__ array -> LDS (address space 3) pointer.
+template <class T>
+__device__ __forceinline__ __attribute__((address_space(3))) T* lds_cast(const void* p) {
+  return (__attribute__((address_space(3))) T*)(p);
+}
+
+constexpr int kStageKeys = 64;  // keys per pipeline stage
+
+template <int D, int BLK>
+struct Tile {
+  static constexpr int kWaves = BLK / 32;          // one wave per 32 query rows
+  static constexpr int kThreads = 64 * kWaves;
+  static constexpr int kPiecesPerRow = D / 8;      // 16-byte pieces per K/V row
+  static constexpr int kSubs = BLK / kStageKeys;   // stages per listed key block
+  static constexpr int kStageBytes = kStageKeys * D * 2;            // one K (or V) stage tile
+  static constexpr int kLoadsPerWave = kStageBytes / 1024 / kWaves; // 1 KiB copies per wave per tile
+  static constexpr int kSteps = D / 16;            // MFMA k-steps of the S product
+  static constexpr int kKeyTiles = kStageKeys / 32;
+  static constexpr int kDTiles = D / 32;           // 32-wide d tiles of O
+};
+
+// Swizzle key of a 256-byte LDS line (16 pieces of 16 bytes); pieces move inside their line only.
+template <int D, bool kIsV>
+__device__ __forceinline__ int swizzle_key(int line) {
+  if (kIsV) return D == 128 ? ((line & 3) << 2) : ((line & 1) << 2);
+  return D == 128 ? (line & 15) : (line & 7);
+}
+
+// LDS byte offset of 16-byte piece p of tile row r.
+template <int D, bool kIsV>
+__device__ __forceinline__ int piece_offset(int r, int p) {
+  const int lin = r * (D / 8) + p;
+  const int line = lin >> 4, slot = lin & 15;
+  return (line << 8) + ((slot ^ swizzle_key<D, kIsV>(line)) << 4);
+}
+
+// One 1 KiB HBM -> LDS copy: lane i's 16 bytes land at LDS address lds_addr + 16*i.
+__device__ __forceinline__ void copy16_to_lds(const void* gptr, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory");
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+  f32x2 f = {a, b};
+  bf16x2 h = __builtin_convertvector(f, bf16x2);
+  return __builtin_bit_cast(uint32_t, h);
+}
+
+template <int D, int BLK>
+__global__ void __launch_bounds__(2 * BLK, 2) radial_fwd_kernel(const FwdArgs a) {
+  using T = Tile<D, BLK>;
+  // [stage buffer][K, V][kStageKeys x D bf16]
+  __shared__ __attribute__((aligned(1024))) char lds[2 * 2 * T::kStageBytes];
+  const uint32_t lds_base = (uint32_t)(uintptr_t)lds_cast<char>(lds);
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lq = lane & 31;   // query column / K row inside a 32-tile
+  const int g = lane >> 5;    // which half of the 16-wide MFMA k-slice this lane feeds
+
+  // Workgroup -> work item.  Consecutive workgroup ids go to different XCDs, so give each XCD
+  // a contiguous run of (head, query block) items: neighbours share K/V tiles in that XCD's L2.
+  const int64_t total = (int64_t)a.B * a.H * a.n_blocks;
+  const int64_t per_xcd = (total + 7) / 8;
+  const int64_t item = (int64_t)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (item >= total) return;
+  const int32_t bh = (int32_t)(item / a.n_blocks);
+  const int32_t qb = a.order ? a.order[item % a.n_blocks] : (int32_t)(item % a.n_blocks);
+  const int32_t b = bh / a.H, h = bh % a.H;
+
+  const __bf16* qp = (const __bf16*)a.q.ptr + (int64_t)b * a.q.sb + (int64_t)h * a.q.sh;
+  const __bf16* kp = (const __bf16*)a.k.ptr + (int64_t)b * a.k.sb + (int64_t)h * a.k.sh;
+  const __bf16* vp = (const __bf16*)a.v.ptr + (int64_t)b * a.v.sb + (int64_t)h * a.v.sh;
+  __bf16* op = (__bf16*)a.o.ptr + (int64_t)b * a.o.sb + (int64_t)h * a.o.sh;
+
+  const int32_t list_lo = __builtin_amdgcn_readfirstlane(a.row_ptr[qb]);
+  const int32_t n_list = __builtin_amdgcn_readfirstlane(a.row_ptr[qb + 1]) - list_lo;
+  const int32_t n_stage = n_list * T::kSubs;
+  const int32_t q_row = qb * BLK + wave * 32 + lq;
+  const bool q_ok = q_row < a.N;
+
+  // Q^T fragments: for k-step t this lane holds Q[q_row, 16t + 8g .. +7].
+  bf16x8 qf[T::kSteps];
+  {
+    const __bf16* src = qp + (int64_t)(q_ok ? q_row : a.N - 1) * a.q.sn + 8 * g;
+#pragma unroll
+    for (int t = 0; t < T::kSteps; ++t) {
+      u32x4 raw = *(const u32x4*)(src + 16 * t);
+      if (!q_ok) raw = u32x4{0u, 0u, 0u, 0u};
+      qf[t] = __builtin_bit_cast(bf16x8, raw);
+    }
+  }
+
+  // The list entries of this row, 64 at a time in one register per lane; cvec is the chunk
+  // being walked, nvec the one after it.
+  const int32_t* cols = a.col_idx + list_lo;
+  int32_t cvec = lane < n_list ? cols[lane] : 0;
+  int32_t nvec = 64 + lane < n_list ? cols[64 + lane] : 0;
+
+  // Which piece of a stage tile each of this lane's copies fetches (fixed for the kernel).
+  int32_t krow[T::kLoadsPerWave], kcol[T::kLoadsPerWave], vrow_[T::kLoadsPerWave], vcol[T::kLoadsPerWave];
+#pragma unroll
+  for (int i = 0; i < T::kLoadsPerWave; ++i) {
+    const int lin = (wave * T::kLoadsPerWave + i) * 64 + lane;  // LDS piece this lane fills
+    const int line = lin >> 4, slot = lin & 15;
+    const int ksrc = (line << 4) + (slot ^ swizzle_key<D, false>(line));
+    const int vsrc = (line << 4) + (slot ^ swizzle_key<D, true>(line));
+    krow[i] = ksrc / T::kPiecesPerRow;
+    kcol[i] = (ksrc % T::kPiecesPerRow) * 8;
+    vrow_[i] = vsrc / T::kPiecesPerRow;
+    vcol[i] = (vsrc % T::kPiecesPerRow) * 8;
+  }
+  // Copies the 64 K rows and V rows starting at key `key0` into stage buffer `buf`.
+  // Rows past N-1 are clamped to N-1; their scores are masked before the softmax.
+  auto issue_stage = [&](int32_t key0, int buf) {
+    const uint32_t kdst = lds_base + buf * 2 * T::kStageBytes + wave * T::kLoadsPerWave * 1024;
+    const uint32_t vdst = kdst + T::kStageBytes;
+#pragma unroll
+    for (int i = 0; i < T::kLoadsPerWave; ++i) {
+      int32_t r = key0 + krow[i];
+      r = r < a.N ? r : a.N - 1;
+      copy16_to_lds(kp + (int64_t)r * a.k.sn + kcol[i], kdst + i * 1024);
+    }
+#pragma unroll
+    for (int i = 0; i < T::kLoadsPerWave; ++i) {
+      int32_t r = key0 + vrow_[i];
+      r = r < a.N ? r : a.N - 1;
+      copy16_to_lds(vp + (int64_t)r * a.v.sn + vcol[i], vdst + i * 1024);
+    }
+  };
+
+  f32x16 o[T::kDTiles];
+#pragma unroll
+  for (int i = 0; i < T::kDTiles; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) o[i][e] = 0.f;
+  float m_run = -INFINITY;  // running row maximum of the raw (unscaled) scores
+  float l_run = 0.f;        // this lane's share of the running row sum
+  const float c = a.scale * 1.4426950408889634f;  // exp(scale*x) = exp2(c*x)
+
+  int32_t key0 = 0;  // first key of the stage about to be computed
+  if (n_stage > 0) {
+    key0 = __builtin_amdgcn_readlane(cvec, 0) * BLK;
+    issue_stage(key0, 0);
+  }
+
+  for (int32_t u = 0; u < n_stage; ++u) {
+    const int buf = u & 1;
+    // First key of stage u+1.
+    int32_t key0_next = 0;
+    const bool has_next = u + 1 < n_stage;
+    if (has_next) {
+      const int32_t e1 = (u + 1) / T::kSubs;
+      if ((u + 1) % T::kSubs == 0 && (e1 & 63) == 0) {  // entering the next chunk of the list
+        cvec = nvec;
+        nvec = e1 + 64 + lane < n_list ? cols[e1 + 64 + lane] : 0;
+      }
+      key0_next = __builtin_amdgcn_readlane(cvec, e1 & 63) * BLK + ((u + 1) % T::kSubs) * kStageKeys;
+    }
+
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's copies of stage u have landed
+    __syncthreads();                                  // ... and everyone's; stage u-1 is fully consumed
+    if (has_next) issue_stage(key0_next, buf ^ 1);
+
+    const char* lds_k = lds + buf * 2 * T::kStageBytes;
+    const char* lds_v = lds_k + T::kStageBytes;
+
+    // ---- S^T = K Q^T -------------------------------------------------------------------
+    f32x16 s[T::kKeyTiles];
+#pragma unroll
+    for (int kt = 0; kt < T::kKeyTiles; ++kt) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) s[kt][e] = 0.f;
+#pragma unroll
+      for (int t = 0; t < T::kSteps; ++t) {
+        const bf16x8 kf = *lds_cast<const bf16x8>(lds_k + piece_offset<D, false>(kt * 32 + lq, 2 * t + g));
+        s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[t], s[kt], 0, 0, 0);
+      }
+    }
+
+    // ---- online softmax ------------------------------------------------------------------
+    // s[kt][e] belongs to key key0 + 32kt + 8(e/4) + 4g + e%4 and query q_row.
+    if (key0 + kStageKeys > a.N) {  // ragged end: keys >= N do not exist
+#pragma unroll
+      for (int kt = 0; kt < T::kKeyTiles; ++kt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int32_t key = key0 + kt * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
+          if (key >= a.N) s[kt][e] = -INFINITY;
+        }
+    }
+    float mx = s[0][0];
+#pragma unroll
+    for (int kt = 0; kt < T::kKeyTiles; ++kt)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[kt][e]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    // A stage that lies entirely past N (second half of a ragged last block) has mx = -inf.
+    const float m_new = fmaxf(m_run, mx);
+    if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {  // some row of this wave got a new maximum
+      const float alpha = m_new > m_run ? __builtin_amdgcn_exp2f((m_run - m_new) * c) : 1.f;
+      l_run *= alpha;
+#pragma unroll
+      for (int i = 0; i < T::kDTiles; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o[i][e] *= alpha;
+      m_run = m_new;
+    }
+    const float mc = m_run == -INFINITY ? 0.f : m_run * c;
+    float psum = 0.f;
+    uint32_t pk[T::kKeyTiles][8];  // P^T as bf16 pairs: B operands of the second product
+#pragma unroll
+    for (int kt = 0; kt < T::kKeyTiles; ++kt)
+#pragma unroll
+      for (int e = 0; e < 16; e += 2) {
+        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kt][e], c, -mc));
+        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kt][e + 1], c, -mc));
+        psum += p0 + p1;
+        pk[kt][e >> 1] = pack_bf16(p0, p1);
+      }
+    l_run += psum;
+
+    // ---- O^T += V^T P^T --------------------------------------------------------------------
+#pragma unroll
+    for (int kt = 0; kt < T::kKeyTiles; ++kt)
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const u32x4 praw = {pk[kt][4 * t], pk[kt][4 * t + 1], pk[kt][4 * t + 2], pk[kt][4 * t + 3]};
+        const bf16x8 pf = __builtin_bit_cast(bf16x8, praw);
+#pragma unroll
+        for (int dt = 0; dt < T::kDTiles; ++dt) {
+          // Lanes 0-15 / 16-31 / 32-47 / 48-63 each transpose a 4-key x 16-d patch: lane i of
+          // a group reads 4 d-contiguous values of key i/4 and receives the 4 keys of d column i.
+          const int i16 = lane & 15;
+          const int vrow = kt * 32 + 16 * t + 4 * g + (i16 >> 2);
+          const int dcol = 32 * dt + 16 * ((lane >> 4) & 1) + 4 * (i16 & 3);
+          const int off0 = piece_offset<D, true>(vrow, dcol >> 3) + ((dcol & 7) << 1);
+          const int off1 = piece_offset<D, true>(vrow + 8, dcol >> 3) + ((dcol & 7) << 1);
+          const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(lds_cast<s16x4>(lds_v + off0));
+          const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(lds_cast<s16x4>(lds_v + off1));
+          const u32x2 a0 = __builtin_bit_cast(u32x2, v0), a1 = __builtin_bit_cast(u32x2, v1);
+          const u32x4 vraw = {a0[0], a0[1], a1[0], a1[1]};
+          o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vraw), pf, o[dt], 0, 0, 0);
+        }
+      }
+    key0 = key0_next;
+  }
+
+  // ---- epilogue: O / l, LSE ----------------------------------------------------------------
+  const float l_tot = l_run + __shfl_xor(l_run, 32);
+  const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+  if (q_ok) {
+    __bf16* dst = op + (int64_t)q_row * a.o.sn;
+#pragma unroll
+    for (int dt = 0; dt < T::kDTiles; ++dt)
+#pragma unroll
+      for (int e4 = 0; e4 < 4; ++e4) {
+        // o[dt][4*e4 + x] is d = 32dt + 8*e4 + 4g + x
+        u32x2 w;
+        w[0] = pack_bf16(o[dt][4 * e4] * inv, o[dt][4 * e4 + 1] * inv);
+        w[1] = pack_bf16(o[dt][4 * e4 + 2] * inv, o[dt][4 * e4 + 3] * inv);
+        *(u32x2*)(dst + 32 * dt + 8 * e4 + 4 * g) = w;
+      }
+    if (a.lse && g == 0) {
+      const int64_t idx = ((int64_t)b * a.H + h) * a.N + q_row;
+      a.lse[idx] = l_tot > 0.f ? m_run * a.scale + __logf(l_tot) : -INFINITY;
+    }
+  }
+}
+
+template <int D, int BLK>
+int launch(const FwdArgs& a, hipStream_t stream) {
+  const int64_t total = (int64_t)a.B * a.H * a.n_blocks;
+  const int64_t grid = 8 * ((total + 7) / 8);
+  if (grid > 0x7fffffffLL) return fail(RADIAL_ESHAPE, "B*H*n_blocks = %lld is too large for one launch", (long long)total);
+  radial_fwd_kernel<D, BLK><<<dim3((unsigned)grid), dim3(Tile<D, BLK>::kThreads), 0, stream>>>(a);
+  RADIAL_HIP_TRY(hipGetLastError());
+  return RADIAL_OK;
+}
+
+}  // namespace
+
+int launch_fwd(int D, int block, const FwdArgs& a, hipStream_t stream) {
+  if (D == 128 && block == 128) return launch<128, 128>(a, stream);
+  if (D == 64 && block == 128) return launch<64, 128>(a, stream);
+  if (D == 128 && block == 64) return launch<128, 64>(a, stream);
+  if (D == 64 && block == 64) return launch<64, 64>(a, stream);
+  return fail(RADIAL_EUNSUPPORTED, "head dimension %d with block %d is not supported", D, block);
+}
+
+}  // namespace radial

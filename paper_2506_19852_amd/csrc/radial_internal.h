@@ -1,0 +1,71 @@
+// Internal declarations shared by the libradial translation units (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "radial.h"
+
+// Device-side description of a block list; owned by radial_mask.
+struct radial_mask {
+  int32_t n_tokens = 0;
+  int32_t block = 0;
+  int32_t n_blocks = 0;  // ceil(n_tokens / block): number of query blocks == number of key blocks
+  int64_t nnz = 0;
+  uint32_t flags = 0;
+  int device = 0;
+  int32_t* d_row_ptr = nullptr;  // [n_blocks + 1]
+  int32_t* d_col_idx = nullptr;  // [nnz]
+  int32_t* d_col_ptr = nullptr;  // [n_blocks + 1]  (transpose; only with RADIAL_MASK_TRANSPOSE)
+  int32_t* d_row_idx = nullptr;  // [nnz]
+  int32_t* d_order = nullptr;    // [n_blocks] query blocks, longest list first (launch order)
+  int32_t* d_order_t = nullptr;  // [n_blocks] key blocks, longest transposed list first
+};
+
+namespace radial {
+
+// Records a message for radial_last_error() and returns `code`.
+int fail(int code, const char* fmt, ...);
+
+#define RADIAL_HIP_TRY(expr)                                                              \
+  do {                                                                                    \
+    hipError_t e_ = (expr);                                                               \
+    if (e_ != hipSuccess)                                                                 \
+      return ::radial::fail(RADIAL_EHIP, "%s failed: %s", #expr, hipGetErrorString(e_));  \
+  } while (0)
+
+struct TensorArg {
+  const void* ptr;
+  int64_t sb, sh, sn;  // element strides
+};
+
+struct FwdArgs {
+  TensorArg q, k, v, o;
+  float* lse;  // may be null
+  const int32_t* row_ptr;
+  const int32_t* col_idx;
+  const int32_t* order;
+  int32_t B, H, N, n_blocks;
+  float scale;
+};
+
+int launch_fwd(int D, int block, const FwdArgs& a, hipStream_t stream);
+
+struct BwdArgs {
+  TensorArg q, k, v, o, dout, dq, dk, dv;
+  const float* lse;
+  float* delta;   // workspace: [B, H, N] rowsum(dO * O)
+  float* dq_acc;  // workspace: [B, H, N, D] fp32 accumulator for dQ
+  const int32_t* row_ptr;
+  const int32_t* col_idx;
+  const int32_t* col_ptr;
+  const int32_t* row_idx;
+  const int32_t* order;
+  const int32_t* order_t;
+  int32_t B, H, N, n_blocks;
+  float scale;
+};
+
+int launch_bwd(int D, int block, const BwdArgs& a, hipStream_t stream);
+
+}  // namespace radial

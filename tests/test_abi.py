@@ -1,0 +1,40 @@
+"""The C-ABI library loads and exports exactly what include/radial.h declares (no GPU needed)."""
+import ctypes
+import os
+import re
+
+from paper_2506_19852_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "radial.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"RADIAL_API\s+[\w\s\*]+?\b(radial_\w+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    names = _declared()
+    assert len(names) == 11 and set(names) == set(binding.EXPORTS)
+    lib = ctypes.CDLL(binding.lib_path())
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_binding_prototypes_and_error_string():
+    lib = binding.load()
+    assert binding.radial_last_error() == "" or isinstance(binding.radial_last_error(), str)
+    # argument errors are detected before any GPU work
+    out = ctypes.c_void_p()
+    rc = lib.radial_mask_build(None, None, ctypes.byref(out))
+    assert rc == -1 and "NULL" in binding.radial_last_error()
+    p = binding.radial_mask_params(4, 16, 100, 1, 0)
+    rc = lib.radial_mask_build(ctypes.byref(p), None, ctypes.byref(out))
+    assert rc == -4 and "block" in binding.radial_last_error()
+    p = binding.radial_mask_params(0, 16, 64, 1, 0)
+    assert lib.radial_mask_build(ctypes.byref(p), None, ctypes.byref(out)) == -1
+    p = binding.radial_mask_params(4, 16, 64, 1, 8)
+    assert lib.radial_mask_build(ctypes.byref(p), None, ctypes.byref(out)) == -1
+    assert lib.radial_attn_bwd_workspace(1, 1, 64, 64, None) == 0
+    lib.radial_mask_free(None)

@@ -1,0 +1,56 @@
+"""Helpers shared by the GPU parity tests: oracle evaluation of sampled query blocks and the
+comparison rule."""
+from __future__ import annotations
+
+import numpy as np
+
+from oracle import attention as oa
+from oracle import build as obuild
+from oracle import mask as om
+
+ATOL = 1e-2     # tolerance of the benchmark spec: |gpu - ref| <= 1e-2 + 1e-2 * |ref|
+RTOL = 1e-2
+REL_INF = 2e-2  # and, because outputs are small, max|err| <= 2e-2 * max|ref| (bf16 rounding is 2^-9)
+
+
+def assert_close(got, ref, what=""):
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (what, got.shape, ref.shape)
+    assert np.isfinite(got).all(), f"{what}: non-finite values"
+    err = np.abs(got - ref)
+    bad = err > ATOL + RTOL * np.abs(ref)
+    assert not bad.any(), f"{what}: {bad.sum()} elements outside 1e-2 abs + 1e-2 rel, max err {err.max():.3e}"
+    scale = np.abs(ref).max()
+    assert err.max() <= REL_INF * scale + 1e-30, f"{what}: max err {err.max():.3e} vs max|ref| {scale:.3e}"
+    return err.max(), scale
+
+
+def oracle_lists(f, s, block, sink, qb_begin=0, qb_end=None):
+    bitmap, _ = obuild.mask_scan(f, s, block, sink, qb_begin, qb_end)
+    return bitmap
+
+
+def oracle_fwd_block(q, k, v, bitmap_row, qb, block, scale):
+    """Eq. 2 for the query rows of block qb of one head.  q, k, v: float arrays [N, D];
+    bitmap_row: bool [n_blocks] listed key blocks.  Returns (O [rows, D], LSE [rows])."""
+    n = q.shape[0]
+    rows = np.arange(qb * block, min(n, (qb + 1) * block))
+    keys = np.flatnonzero(om.expand_block_row(bitmap_row, block, n))
+    if keys.size == 0:
+        return np.zeros((rows.size, q.shape[1])), np.full(rows.size, -np.inf)
+    o, lse, _ = oa.attention_rows_keyset(q[rows], k, v, keys, scale)
+    return o, lse
+
+
+def sample_qblocks(n_blocks, row_len, s, block, count, seed):
+    """A fixed sample of query blocks: first, last (ragged), shortest and longest rows, blocks
+    that straddle a frame boundary, plus seeded random ones."""
+    rng = np.random.default_rng(seed)
+    picks = {0, n_blocks - 1, int(np.argmin(row_len)), int(np.argmax(row_len))}
+    straddle = [qb for qb in range(n_blocks) if (qb * block) // s != min((qb + 1) * block - 1, n_blocks * block) // s]
+    for qb in straddle[:: max(1, len(straddle) // 6)][:6]:
+        picks.add(qb)
+    while len(picks) < min(count, n_blocks):
+        picks.add(int(rng.integers(0, n_blocks)))
+    return sorted(picks)
