@@ -70,6 +70,8 @@ def main():
     ap.add_argument("--workload", default="cfg3_hunyuan720p")
     ap.add_argument("--dense-steps", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain device copy of q (known size) so a rocprofv3 --pmc run can scale FETCH_SIZE/WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -108,6 +110,9 @@ def main():
             torch.cuda.synchronize()
             m.free()
 
+    if args.copy_probe:
+        out.copy_(x["q"])     # reads and writes q.numel()*2 bytes
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
