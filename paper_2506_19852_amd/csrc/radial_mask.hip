@@ -11,6 +11,7 @@
 // LDS; a count pass, an exclusive scan and a fill pass turn the bitmaps into compressed lists.
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <new>
@@ -34,6 +35,7 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kMaxWords = 15 * 1024;  // 60 KiB of LDS bitmap: up to 491 520 key blocks
+constexpr int kOrderChunk = 1;        // blocks per run of the launch order
 
 struct MaskGeom {
   int32_t f, s, block, sink, n, nb;
@@ -210,17 +212,23 @@ __global__ void __launch_bounds__(kThreads) transpose_fill_kernel(const int32_t*
   }
 }
 
-// order[rank] = i where rank sorts list lengths descending (ties: lower index first).
-__global__ void order_kernel(const int32_t* ptr, int32_t nb, int32_t* order) {
-  const int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= nb) return;
-  const int32_t len = ptr[i + 1] - ptr[i];
-  int32_t rank = 0;
-  for (int32_t j = 0; j < nb; ++j) {
-    const int32_t lj = ptr[j + 1] - ptr[j];
-    rank += (lj > len || (lj == len && j < i)) ? 1 : 0;
+// Launch order: runs of `chunk` consecutive blocks, heaviest run first (ties: lower index
+// first), natural order inside a run.  Consecutive blocks of a run have nearly the same
+// lists, so workgroups that run side by side share K/V tiles in L2, while light runs end up
+// last and shorten the tail of the launch.
+__global__ void order_kernel(const int32_t* ptr, int32_t nb, int32_t chunk, int32_t* order) {
+  const int32_t nchunks = (nb + chunk - 1) / chunk;
+  for (int32_t c = blockIdx.x * blockDim.x + threadIdx.x; c < nchunks; c += gridDim.x * blockDim.x) {
+    const int32_t lo = c * chunk, hi = lo + chunk < nb ? lo + chunk : nb;
+    const int32_t w = ptr[hi] - ptr[lo];
+    int32_t start = 0;
+    for (int32_t o = 0; o < nchunks; ++o) {
+      const int32_t olo = o * chunk, ohi = olo + chunk < nb ? olo + chunk : nb;
+      const int32_t ow = ptr[ohi] - ptr[olo];
+      if (ow > w || (ow == w && o < c)) start += ohi - olo;
+    }
+    for (int32_t i = lo; i < hi; ++i) order[start + (i - lo)] = i;
   }
-  order[rank] = i;
 }
 
 int check_common(int64_t n_tokens, int32_t block, uint32_t flags) {
@@ -236,9 +244,11 @@ int check_common(int64_t n_tokens, int32_t block, uint32_t flags) {
 // Shared tail of the three constructors: transposed lists (optional) and launch orders.
 int finish_mask(radial_mask* m, hipStream_t st) {
   const int32_t nb = m->n_blocks;
-  const int grid_nb = (nb + kThreads - 1) / kThreads;
+  int32_t chunk = kOrderChunk;
+  if (const char* e = getenv("RADIAL_ORDER_CHUNK")) chunk = atoi(e) > 0 ? atoi(e) : nb;  // tuning aid
+  const int grid_nb = ((nb + chunk - 1) / chunk + kThreads - 1) / kThreads;
   RADIAL_HIP_TRY(hipMalloc(&m->d_order, sizeof(int32_t) * nb));
-  order_kernel<<<grid_nb, kThreads, 0, st>>>(m->d_row_ptr, nb, m->d_order);
+  order_kernel<<<grid_nb, kThreads, 0, st>>>(m->d_row_ptr, nb, chunk, m->d_order);
   RADIAL_HIP_TRY(hipGetLastError());
   if (m->flags & RADIAL_MASK_TRANSPOSE) {
     long long* d_total = nullptr;
@@ -249,7 +259,7 @@ int finish_mask(radial_mask* m, hipStream_t st) {
     transpose_count_kernel<<<nb, kThreads, 0, st>>>(m->d_row_ptr, m->d_col_idx, nb, m->d_col_ptr);
     scan_kernel<<<1, kThreads, 0, st>>>(m->d_col_ptr, nb, d_total);
     transpose_fill_kernel<<<nb, kThreads, 0, st>>>(m->d_row_ptr, m->d_col_idx, nb, m->d_col_ptr, m->d_row_idx);
-    order_kernel<<<grid_nb, kThreads, 0, st>>>(m->d_col_ptr, nb, m->d_order_t);
+    order_kernel<<<grid_nb, kThreads, 0, st>>>(m->d_col_ptr, nb, chunk, m->d_order_t);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess) e = hipStreamSynchronize(st);
     (void)hipFree(d_total);
