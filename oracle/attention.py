@@ -80,3 +80,28 @@ def attention_bwd_rows(q_rows, k, v, visible, scale, do_rows):
     dq = scale * (ds @ kk)
     dk = scale * (ds.T @ q)
     return dq, dk, dv, ds
+
+
+def attention_bwd_keyset(q_rows, k, v, keys, scale, do_rows, cols=None):
+    """Gradient of Eq. 2 for query rows that all see exactly the key set ``keys``.
+
+    Same formulas as attention_bwd_rows on the gathered K[keys], V[keys].  Returns
+    (dQ [r, D], dK_part [len(sel), D], dV_part [len(sel), D]) where ``sel`` are the
+    positions inside ``keys`` listed in ``cols`` (all of them when cols is None): the dK/dV
+    contributions of these query rows to those keys only.  The softmax, O and D_q still run
+    over the whole key set."""
+    keys = np.asarray(keys, dtype=np.int64)
+    q = np.asarray(q_rows, dtype=np.float64)
+    kk = np.asarray(k)[keys].astype(np.float64)
+    vv = np.asarray(v)[keys].astype(np.float64)
+    do = np.asarray(do_rows, dtype=np.float64)
+    vis = np.ones((q.shape[0], keys.size), dtype=bool)
+    o, _, p = attention_rows(q, kk, vv, vis, scale)
+    delta = (do * o).sum(axis=1, keepdims=True)
+    dp = do @ vv.T
+    ds = p * (dp - delta)
+    dq = scale * (ds @ kk)
+    sel = np.arange(keys.size) if cols is None else np.asarray(cols, dtype=np.int64)
+    dv = p[:, sel].T @ do
+    dk = scale * (ds[:, sel].T @ q)
+    return dq, dk, dv

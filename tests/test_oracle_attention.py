@@ -169,3 +169,19 @@ def test_backward_row_parts_add_up():
     dq2, dk2, dv2, _ = oa.attention_bwd_rows(q[4:], k, v, vis[4:], 0.4, g[4:])
     assert np.allclose(np.concatenate([dq1, dq2]), dq, rtol=1e-13)
     assert np.allclose(dk1 + dk2, dk, rtol=1e-12, atol=1e-14) and np.allclose(dv1 + dv2, dv, rtol=1e-12, atol=1e-14)
+
+
+def test_backward_keyset_form_equals_bool_form():
+    rng = np.random.default_rng(9)
+    r, n, d = 7, 40, 8
+    q, k, v, g = _rand(rng, r, d), _rand(rng, n, d), _rand(rng, n, d), _rand(rng, r, d)
+    keys = np.array([0, 1, 5, 6, 7, 20, 21, 39])
+    vis = np.zeros((r, n), bool)
+    vis[:, keys] = True
+    dq, dk, dv, _ = oa.attention_bwd_rows(q, k, v, vis, 0.3, g)
+    dq2, dk2, dv2 = oa.attention_bwd_keyset(q, k, v, keys, 0.3, g)
+    assert np.allclose(dq, dq2, rtol=1e-12, atol=1e-14)
+    assert np.allclose(dk[keys], dk2, rtol=1e-12, atol=1e-14) and np.allclose(dv[keys], dv2, rtol=1e-12, atol=1e-14)
+    assert (dk[np.setdiff1d(np.arange(n), keys)] == 0).all()
+    dq3, dk3, dv3 = oa.attention_bwd_keyset(q, k, v, keys, 0.3, g, cols=[2, 3, 4])
+    assert np.allclose(dq3, dq2) and np.allclose(dk3, dk2[2:5]) and np.allclose(dv3, dv2[2:5])

@@ -13,15 +13,22 @@ RTOL = 1e-2
 REL_INF = 2e-2  # and, because outputs are small, max|err| <= 2e-2 * max|ref| (bf16 rounding is 2^-9)
 
 
-def assert_close(got, ref, what=""):
+def assert_close(got, ref, what="", scaled_atol=False):
+    """|got - ref| <= 1e-2 + 1e-2*|ref| element-wise and max|err| <= 2e-2*max|ref|.
+
+    scaled_atol: for stress inputs whose results are far larger than 1 (peaked softmax rows with
+    4x-6x larger queries) the absolute term is 1e-2*max|ref| instead: P and dS are rounded to
+    bf16 (relative 2^-9) before the second products, so the error of a sum scales with its
+    largest terms, not with the element it lands on."""
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
     assert got.shape == ref.shape, (what, got.shape, ref.shape)
     assert np.isfinite(got).all(), f"{what}: non-finite values"
     err = np.abs(got - ref)
-    bad = err > ATOL + RTOL * np.abs(ref)
-    assert not bad.any(), f"{what}: {bad.sum()} elements outside 1e-2 abs + 1e-2 rel, max err {err.max():.3e}"
     scale = np.abs(ref).max()
+    atol = max(ATOL, ATOL * scale) if scaled_atol else ATOL
+    bad = err > atol + RTOL * np.abs(ref)
+    assert not bad.any(), f"{what}: {bad.sum()} elements outside {atol:.1e} abs + 1e-2 rel, max err {err.max():.3e}"
     assert err.max() <= REL_INF * scale + 1e-30, f"{what}: max err {err.max():.3e} vs max|ref| {scale:.3e}"
     return err.max(), scale
 
