@@ -12,6 +12,7 @@ int check_tensor(const char* name, const radial_tensor& t, int32_t D) {
   if (((uintptr_t)t.ptr & 15u) != 0) return fail(RADIAL_ESHAPE, "%s.ptr is not 16-byte aligned", name);
   if (t.stride_n < D || (t.stride_n & 7) || (t.stride_h & 7) || (t.stride_b & 7) || t.stride_h < 0 || t.stride_b < 0)
     return fail(RADIAL_ESHAPE, "%s strides must be non-negative multiples of 8 elements with stride_n >= D", name);
+  if (t.stride_n >= (1 << 22)) return fail(RADIAL_ESHAPE, "%s.stride_n must be below 2^22 elements", name);
   return RADIAL_OK;
 }
 

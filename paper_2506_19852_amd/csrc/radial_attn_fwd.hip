@@ -74,6 +74,13 @@ __device__ __forceinline__ void copy16_to_lds(const void* gptr, uint32_t lds_add
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory");
 }
 
+// Same copy with the address split into a wave-uniform 64-bit base (SGPRs) and a per-lane
+// 32-bit byte offset, so that walking to the next tile costs scalar arithmetic only.
+__device__ __forceinline__ void copy16_to_lds(const void* base, uint32_t byte_offset, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               ::"s"(lds_addr), "v"(byte_offset), "s"(base) : "memory");
+}
+
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   f32x2 f = {a, b};
   bf16x2 h = __builtin_convertvector(f, bf16x2);
@@ -131,8 +138,10 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_fwd_kernel(const FwdArgs a)
   int32_t cvec = lane < n_list ? cols[lane] : 0;
   int32_t nvec = 64 + lane < n_list ? cols[64 + lane] : 0;
 
-  // Which piece of a stage tile each of this lane's copies fetches (fixed for the kernel).
+  // Which piece of a stage tile each of this lane's copies fetches (fixed for the kernel),
+  // as a byte offset from the first row of the tile.
   int32_t krow[T::kLoadsPerWave], kcol[T::kLoadsPerWave], vrow_[T::kLoadsPerWave], vcol[T::kLoadsPerWave];
+  uint32_t koff[T::kLoadsPerWave], voff[T::kLoadsPerWave];
 #pragma unroll
   for (int i = 0; i < T::kLoadsPerWave; ++i) {
     const int lin = (wave * T::kLoadsPerWave + i) * 64 + lane;  // LDS piece this lane fills
@@ -143,23 +152,33 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_fwd_kernel(const FwdArgs a)
     kcol[i] = (ksrc % T::kPiecesPerRow) * 8;
     vrow_[i] = vsrc / T::kPiecesPerRow;
     vcol[i] = (vsrc % T::kPiecesPerRow) * 8;
+    koff[i] = (uint32_t)(krow[i] * (int32_t)a.k.sn + kcol[i]) * 2u;
+    voff[i] = (uint32_t)(vrow_[i] * (int32_t)a.v.sn + vcol[i]) * 2u;
   }
   // Copies the 64 K rows and V rows starting at key `key0` into stage buffer `buf`.
   // Rows past N-1 are clamped to N-1; their scores are masked before the softmax.
   auto issue_stage = [&](int32_t key0, int buf) {
     const uint32_t kdst = lds_base + buf * 2 * T::kStageBytes + wave * T::kLoadsPerWave * 1024;
     const uint32_t vdst = kdst + T::kStageBytes;
+    const __bf16* kbase = kp + (int64_t)key0 * a.k.sn;  // wave-uniform
+    const __bf16* vbase = vp + (int64_t)key0 * a.v.sn;
+    if (key0 + kStageKeys <= a.N) {
 #pragma unroll
-    for (int i = 0; i < T::kLoadsPerWave; ++i) {
-      int32_t r = key0 + krow[i];
-      r = r < a.N ? r : a.N - 1;
-      copy16_to_lds(kp + (int64_t)r * a.k.sn + kcol[i], kdst + i * 1024);
-    }
+      for (int i = 0; i < T::kLoadsPerWave; ++i) copy16_to_lds(kbase, koff[i], kdst + i * 1024);
 #pragma unroll
-    for (int i = 0; i < T::kLoadsPerWave; ++i) {
-      int32_t r = key0 + vrow_[i];
-      r = r < a.N ? r : a.N - 1;
-      copy16_to_lds(vp + (int64_t)r * a.v.sn + vcol[i], vdst + i * 1024);
+      for (int i = 0; i < T::kLoadsPerWave; ++i) copy16_to_lds(vbase, voff[i], vdst + i * 1024);
+    } else {  // ragged end of the sequence
+      const int32_t last = a.N - 1 - key0;  // >= 0: a listed block starts below N; a stage past N reads row N-1
+#pragma unroll
+      for (int i = 0; i < T::kLoadsPerWave; ++i) {
+        const int32_t r = krow[i] < last ? krow[i] : last;
+        copy16_to_lds(kp + ((int64_t)key0 + r) * a.k.sn + kcol[i], kdst + i * 1024);
+      }
+#pragma unroll
+      for (int i = 0; i < T::kLoadsPerWave; ++i) {
+        const int32_t r = vrow_[i] < last ? vrow_[i] : last;
+        copy16_to_lds(vp + ((int64_t)key0 + r) * a.v.sn + vcol[i], vdst + i * 1024);
+      }
     }
   };
 
