@@ -247,7 +247,10 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_fwd_kernel(const FwdArgs a)
     for (int kt = 0; kt < T::kKeyTiles; ++kt)
 #pragma unroll
       for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[kt][e]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    {  // exchange with lane^32 (the other half of the row's keys) without going through LDS
+      const auto sw = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(uint32_t, mx), __builtin_bit_cast(uint32_t, mx), false, false);
+      mx = fmaxf(__builtin_bit_cast(float, sw[0]), __builtin_bit_cast(float, sw[1]));
+    }
     // A stage that lies entirely past N (second half of a ragged last block) has mx = -inf.
     const float m_new = fmaxf(m_run, mx);
     if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {  // some row of this wave got a new maximum
