@@ -46,7 +46,8 @@ extern "C" int radial_attn_fwd(int32_t B, int32_t H, int32_t N, int32_t D, radia
   a.lse = lse;
   a.row_ptr = mask->d_row_ptr;
   a.col_idx = mask->d_col_idx;
-  a.order = mask->d_order;
+  a.slice = mask->d_slice;
+  a.max_slice = mask->max_slice;
   a.B = B; a.H = H; a.N = N; a.n_blocks = mask->n_blocks;
   a.scale = scale;
   return launch_fwd(D, mask->block, a, (hipStream_t)hip_stream);
@@ -85,7 +86,7 @@ extern "C" int radial_attn_bwd(int32_t B, int32_t H, int32_t N, int32_t D, radia
   a.dq_acc = (float*)((char*)workspace + delta_bytes(B, H, N));
   a.row_ptr = mask->d_row_ptr; a.col_idx = mask->d_col_idx;
   a.col_ptr = mask->d_col_ptr; a.row_idx = mask->d_row_idx;
-  a.order = mask->d_order; a.order_t = mask->d_order_t;
+  a.slice_t = mask->d_slice_t; a.max_slice_t = mask->max_slice_t;
   a.B = B; a.H = H; a.N = N; a.n_blocks = mask->n_blocks;
   a.scale = scale;
   return launch_bwd(D, mask->block, a, (hipStream_t)hip_stream);

@@ -105,13 +105,14 @@ __global__ void __launch_bounds__(2 * BLK, 1) radial_bwd_kernel(const BwdArgs a)
   const int i16 = lane & 15;
   const int half16 = (lane >> 4) & 1;
 
-  // work item: XCD x owns a contiguous run of (head, key block) items
-  const int64_t total = (int64_t)a.B * a.H * a.n_blocks;
-  const int64_t per_xcd = (total + 7) / 8;
-  const int64_t item = (int64_t)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-  if (item >= total) return;
-  const int32_t bh = (int32_t)(item / a.n_blocks);
-  const int32_t kb = a.order_t ? a.order_t[item % a.n_blocks] : (int32_t)(item % a.n_blocks);
+  // work item: XCD x owns the key blocks [slice_t[x], slice_t[x+1]) of every (batch, head)
+  const int32_t xcd = blockIdx.x & 7;
+  const int32_t s0 = a.slice_t[xcd];
+  const int32_t slice_len = a.slice_t[xcd + 1] - s0;
+  const int64_t idx = blockIdx.x >> 3;
+  if (slice_len <= 0 || idx >= (int64_t)slice_len * a.B * a.H) return;
+  const int32_t bh = (int32_t)(idx / slice_len);
+  const int32_t kb = s0 + (int32_t)(idx % slice_len);
   const int32_t b = bh / a.H, h = bh % a.H;
 
   const __bf16* qp = (const __bf16*)a.q.ptr + (int64_t)b * a.q.sb + (int64_t)h * a.q.sh;
@@ -319,8 +320,7 @@ int launch(const BwdArgs& a, hipStream_t stream) {
   const int64_t rows = (int64_t)a.B * a.H * a.N;
   const int rows_per_block = 256 / (D / 8);
   const int64_t prep_grid = (rows + rows_per_block - 1) / rows_per_block;
-  const int64_t total = (int64_t)a.B * a.H * a.n_blocks;
-  const int64_t grid = 8 * ((total + 7) / 8);
+  const int64_t grid = 8LL * a.B * a.H * a.max_slice_t;
   if (prep_grid > 0x7fffffffLL || grid > 0x7fffffffLL) return fail(RADIAL_ESHAPE, "problem too large for one launch");
   static bool configured = false;  // per template instance
   if (!configured) {
@@ -329,7 +329,7 @@ int launch(const BwdArgs& a, hipStream_t stream) {
     configured = true;
   }
   bwd_prepare_kernel<D><<<dim3((unsigned)prep_grid), dim3(256), 0, stream>>>(a);
-  radial_bwd_kernel<D, BLK><<<dim3((unsigned)grid), dim3(T::kThreads), T::kLdsBytes, stream>>>(a);
+  if (grid > 0) radial_bwd_kernel<D, BLK><<<dim3((unsigned)grid), dim3(T::kThreads), T::kLdsBytes, stream>>>(a);
   bwd_finish_kernel<D><<<dim3((unsigned)prep_grid), dim3(256), 0, stream>>>(a);
   RADIAL_HIP_TRY(hipGetLastError());
   return RADIAL_OK;

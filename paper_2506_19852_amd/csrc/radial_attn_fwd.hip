@@ -99,14 +99,17 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_fwd_kernel(const FwdArgs a)
   const int lq = lane & 31;   // query column / K row inside a 32-tile
   const int g = lane >> 5;    // which half of the 16-wide MFMA k-slice this lane feeds
 
-  // Workgroup -> work item.  Consecutive workgroup ids go to different XCDs, so give each XCD
-  // a contiguous run of (head, query block) items: neighbours share K/V tiles in that XCD's L2.
-  const int64_t total = (int64_t)a.B * a.H * a.n_blocks;
-  const int64_t per_xcd = (total + 7) / 8;
-  const int64_t item = (int64_t)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-  if (item >= total) return;
-  const int32_t bh = (int32_t)(item / a.n_blocks);
-  const int32_t qb = a.order ? a.order[item % a.n_blocks] : (int32_t)(item % a.n_blocks);
+  // Workgroup -> work item.  Consecutive workgroup ids go to different XCDs; XCD x owns the
+  // query blocks [slice[x], slice[x+1]) and walks them head after head, so all XCDs work on
+  // the same head at the same time (its K/V stay in the shared last-level cache) and
+  // neighbouring workgroups of an XCD share K/V tiles in that XCD's L2.
+  const int32_t xcd = blockIdx.x & 7;
+  const int32_t s0 = a.slice[xcd];
+  const int32_t slice_len = a.slice[xcd + 1] - s0;
+  const int64_t idx = blockIdx.x >> 3;
+  if (slice_len <= 0 || idx >= (int64_t)slice_len * a.B * a.H) return;
+  const int32_t bh = (int32_t)(idx / slice_len);
+  const int32_t qb = s0 + (int32_t)(idx % slice_len);
   const int32_t b = bh / a.H, h = bh % a.H;
 
   const __bf16* qp = (const __bf16*)a.q.ptr + (int64_t)b * a.q.sb + (int64_t)h * a.q.sh;
@@ -326,9 +329,9 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_fwd_kernel(const FwdArgs a)
 
 template <int D, int BLK>
 int launch(const FwdArgs& a, hipStream_t stream) {
-  const int64_t total = (int64_t)a.B * a.H * a.n_blocks;
-  const int64_t grid = 8 * ((total + 7) / 8);
-  if (grid > 0x7fffffffLL) return fail(RADIAL_ESHAPE, "B*H*n_blocks = %lld is too large for one launch", (long long)total);
+  const int64_t grid = 8LL * a.B * a.H * a.max_slice;
+  if (grid > 0x7fffffffLL) return fail(RADIAL_ESHAPE, "B*H*n_blocks is too large for one launch");
+  if (grid == 0) return RADIAL_OK;
   radial_fwd_kernel<D, BLK><<<dim3((unsigned)grid), dim3(Tile<D, BLK>::kThreads), 0, stream>>>(a);
   RADIAL_HIP_TRY(hipGetLastError());
   return RADIAL_OK;

@@ -18,8 +18,13 @@ struct radial_mask {
   int32_t* d_col_idx = nullptr;  // [nnz]
   int32_t* d_col_ptr = nullptr;  // [n_blocks + 1]  (transpose; only with RADIAL_MASK_TRANSPOSE)
   int32_t* d_row_idx = nullptr;  // [nnz]
-  int32_t* d_order = nullptr;    // [n_blocks] query blocks, longest list first (launch order)
-  int32_t* d_order_t = nullptr;  // [n_blocks] key blocks, longest transposed list first
+  // Launch partition: XCD x of the 8 works on query blocks [slice[x], slice[x+1]) of every
+  // (batch, head), so that all XCDs are on the same head at the same time (its K/V then sit
+  // in the shared last-level cache) and carry equal weight.  Same for key blocks (backward).
+  int32_t* d_slice = nullptr;    // [9]
+  int32_t* d_slice_t = nullptr;  // [9]
+  int32_t max_slice = 0;         // longest slice, in blocks (host copy, sizes the grid)
+  int32_t max_slice_t = 0;
 };
 
 namespace radial {
@@ -44,7 +49,8 @@ struct FwdArgs {
   float* lse;  // may be null
   const int32_t* row_ptr;
   const int32_t* col_idx;
-  const int32_t* order;
+  const int32_t* slice;  // [9] query-block partition over the XCDs
+  int32_t max_slice;
   int32_t B, H, N, n_blocks;
   float scale;
 };
@@ -60,8 +66,8 @@ struct BwdArgs {
   const int32_t* col_idx;
   const int32_t* col_ptr;
   const int32_t* row_idx;
-  const int32_t* order;
-  const int32_t* order_t;
+  const int32_t* slice_t;  // [9] key-block partition over the XCDs
+  int32_t max_slice_t;
   int32_t B, H, N, n_blocks;
   float scale;
 };

@@ -11,7 +11,6 @@
 // LDS; a count pass, an exclusive scan and a fill pass turn the bitmaps into compressed lists.
 #include <stdarg.h>
 #include <stdio.h>
-#include <stdlib.h>
 #include <string.h>
 
 #include <new>
@@ -35,7 +34,6 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kMaxWords = 15 * 1024;  // 60 KiB of LDS bitmap: up to 491 520 key blocks
-constexpr int kOrderChunk = 1;        // blocks per run of the launch order
 
 struct MaskGeom {
   int32_t f, s, block, sink, n, nb;
@@ -212,23 +210,22 @@ __global__ void __launch_bounds__(kThreads) transpose_fill_kernel(const int32_t*
   }
 }
 
-// Launch order: runs of `chunk` consecutive blocks, heaviest run first (ties: lower index
-// first), natural order inside a run.  Consecutive blocks of a run have nearly the same
-// lists, so workgroups that run side by side share K/V tiles in L2, while light runs end up
-// last and shorten the tail of the launch.
-__global__ void order_kernel(const int32_t* ptr, int32_t nb, int32_t chunk, int32_t* order) {
-  const int32_t nchunks = (nb + chunk - 1) / chunk;
-  for (int32_t c = blockIdx.x * blockDim.x + threadIdx.x; c < nchunks; c += gridDim.x * blockDim.x) {
-    const int32_t lo = c * chunk, hi = lo + chunk < nb ? lo + chunk : nb;
-    const int32_t w = ptr[hi] - ptr[lo];
-    int32_t start = 0;
-    for (int32_t o = 0; o < nchunks; ++o) {
-      const int32_t olo = o * chunk, ohi = olo + chunk < nb ? olo + chunk : nb;
-      const int32_t ow = ptr[ohi] - ptr[olo];
-      if (ow > w || (ow == w && o < c)) start += ohi - olo;
-    }
-    for (int32_t i = lo; i < hi; ++i) order[start + (i - lo)] = i;
+// Launch partition: slice[k] = first block r whose weight prefix W(r) = ptr[r] + kItemCost*r
+// reaches k/8 of the total (slice[0] = 0, slice[8] = nb): 8 runs of consecutive blocks with
+// equal work, one per XCD.  kItemCost stands for the fixed cost of a work item (loading Q,
+// storing O) in units of one listed block.
+constexpr int kItemCost = 4;
+__global__ void slice_kernel(const int32_t* ptr, int32_t nb, int32_t* slice) {
+  const int k = threadIdx.x;
+  if (k > 8) return;
+  const long long total = (long long)ptr[nb] + (long long)kItemCost * nb;
+  const long long target = (total * k + 7) / 8;
+  int32_t lo = 0, hi = nb;  // smallest r in [0, nb] with W(r) >= target
+  while (lo < hi) {
+    const int32_t mid = lo + ((hi - lo) >> 1);
+    if ((long long)ptr[mid] + (long long)kItemCost * mid >= target) hi = mid; else lo = mid + 1;
   }
+  slice[k] = k == 8 ? nb : (k == 0 ? 0 : lo);
 }
 
 int check_common(int64_t n_tokens, int32_t block, uint32_t flags) {
@@ -244,26 +241,30 @@ int check_common(int64_t n_tokens, int32_t block, uint32_t flags) {
 // Shared tail of the three constructors: transposed lists (optional) and launch orders.
 int finish_mask(radial_mask* m, hipStream_t st) {
   const int32_t nb = m->n_blocks;
-  int32_t chunk = kOrderChunk;
-  if (const char* e = getenv("RADIAL_ORDER_CHUNK")) chunk = atoi(e) > 0 ? atoi(e) : nb;  // tuning aid
-  const int grid_nb = ((nb + chunk - 1) / chunk + kThreads - 1) / kThreads;
-  RADIAL_HIP_TRY(hipMalloc(&m->d_order, sizeof(int32_t) * nb));
-  order_kernel<<<grid_nb, kThreads, 0, st>>>(m->d_row_ptr, nb, chunk, m->d_order);
+  int32_t h_slice[9];
+  RADIAL_HIP_TRY(hipMalloc(&m->d_slice, sizeof(int32_t) * 9));
+  slice_kernel<<<1, 64, 0, st>>>(m->d_row_ptr, nb, m->d_slice);
   RADIAL_HIP_TRY(hipGetLastError());
+  RADIAL_HIP_TRY(hipMemcpyAsync(h_slice, m->d_slice, sizeof h_slice, hipMemcpyDeviceToHost, st));
+  RADIAL_HIP_TRY(hipStreamSynchronize(st));
+  for (int k = 0; k < 8; ++k) m->max_slice = h_slice[k + 1] - h_slice[k] > m->max_slice ? h_slice[k + 1] - h_slice[k] : m->max_slice;
   if (m->flags & RADIAL_MASK_TRANSPOSE) {
     long long* d_total = nullptr;
     RADIAL_HIP_TRY(hipMalloc(&m->d_col_ptr, sizeof(int32_t) * (nb + 1)));
     RADIAL_HIP_TRY(hipMalloc(&m->d_row_idx, sizeof(int32_t) * (m->nnz > 0 ? m->nnz : 1)));
-    RADIAL_HIP_TRY(hipMalloc(&m->d_order_t, sizeof(int32_t) * nb));
+    RADIAL_HIP_TRY(hipMalloc(&m->d_slice_t, sizeof(int32_t) * 9));
     RADIAL_HIP_TRY(hipMalloc(&d_total, sizeof(long long)));
     transpose_count_kernel<<<nb, kThreads, 0, st>>>(m->d_row_ptr, m->d_col_idx, nb, m->d_col_ptr);
     scan_kernel<<<1, kThreads, 0, st>>>(m->d_col_ptr, nb, d_total);
     transpose_fill_kernel<<<nb, kThreads, 0, st>>>(m->d_row_ptr, m->d_col_idx, nb, m->d_col_ptr, m->d_row_idx);
-    order_kernel<<<grid_nb, kThreads, 0, st>>>(m->d_col_ptr, nb, chunk, m->d_order_t);
+    slice_kernel<<<1, 64, 0, st>>>(m->d_col_ptr, nb, m->d_slice_t);
     hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = hipMemcpyAsync(h_slice, m->d_slice_t, sizeof h_slice, hipMemcpyDeviceToHost, st);
     if (e == hipSuccess) e = hipStreamSynchronize(st);
     (void)hipFree(d_total);
     if (e != hipSuccess) return fail(RADIAL_EHIP, "transpose kernels failed: %s", hipGetErrorString(e));
+    for (int k = 0; k < 8; ++k)
+      m->max_slice_t = h_slice[k + 1] - h_slice[k] > m->max_slice_t ? h_slice[k + 1] - h_slice[k] : m->max_slice_t;
   }
   RADIAL_HIP_TRY(hipStreamSynchronize(st));
   return RADIAL_OK;
@@ -282,8 +283,8 @@ extern "C" void radial_mask_free(radial_mask* m) {
   (void)hipFree(m->d_col_idx);
   (void)hipFree(m->d_col_ptr);
   (void)hipFree(m->d_row_idx);
-  (void)hipFree(m->d_order);
-  (void)hipFree(m->d_order_t);
+  (void)hipFree(m->d_slice);
+  (void)hipFree(m->d_slice_t);
   delete m;
 }
 
