@@ -21,6 +21,14 @@ if ROOT not in sys.path:
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 
+# HBM-side bytes per forward launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes in
+# profiles/ (FETCH_SIZE scaled by 2.0, WRITE_SIZE by 1.0: what the same counters read for a
+# streaming kernel of known size in the same run).  None where no pass has been recorded.
+MEASURED_TRAFFIC_BYTES = {
+    "cfg3_hunyuan720p": 2.35715e8 * 1024 * 2.0 + 7.24646e5 * 1024,
+    "cfg5_wan480p_4x_bwd": 3.82715e8 * 1024 * 2.0 + 1.28485e6 * 1024,
+}
+
 
 def effective_flops(row_ptr, col_idx, n_tokens, block, D, heads):
     """4*D*sum over listed pairs of rows(qb)*cols(kb): both products, real tokens only."""
@@ -162,7 +170,7 @@ def main():
         "speedup_vs_dense": round(dense_ms / kernel_ms, 3),
         "block_ratio_dense_over_radial": round(dense_flops / fwd_flops, 3),
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                     "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
                      "kernel": "radial_fwd_kernel", "flops_per_launch": fwd_flops},
     }
     if not args.no_cpu_baseline:
