@@ -53,7 +53,7 @@ extern "C" int radial_attn_fwd(int32_t B, int32_t H, int32_t N, int32_t D, radia
   return launch_fwd(D, mask->block, a, (hipStream_t)hip_stream);
 }
 
-// Workspace layout: delta [B*H*N] fp32, then (256-byte aligned) dQ accumulator [B*H*N*D] fp32.
+// Workspace layout: delta [B*H*N] fp32.
 static size_t delta_bytes(int32_t B, int32_t H, int32_t N) {
   const size_t raw = (size_t)B * H * N * sizeof(float);
   return (raw + 255) & ~(size_t)255;
@@ -61,7 +61,7 @@ static size_t delta_bytes(int32_t B, int32_t H, int32_t N) {
 
 extern "C" size_t radial_attn_bwd_workspace(int32_t B, int32_t H, int32_t N, int32_t D, const radial_mask* mask) {
   if (!mask || B < 1 || H < 1 || N < 1 || (D != 64 && D != 128) || N != mask->n_tokens) return 0;
-  return delta_bytes(B, H, N) + (size_t)B * H * N * D * sizeof(float);
+  return delta_bytes(B, H, N);
 }
 
 extern "C" int radial_attn_bwd(int32_t B, int32_t H, int32_t N, int32_t D, radial_tensor q, radial_tensor k,
@@ -83,9 +83,9 @@ extern "C" int radial_attn_bwd(int32_t B, int32_t H, int32_t N, int32_t D, radia
   a.dq = arg(dq); a.dk = arg(dk); a.dv = arg(dv);
   a.lse = lse;
   a.delta = (float*)workspace;
-  a.dq_acc = (float*)((char*)workspace + delta_bytes(B, H, N));
   a.row_ptr = mask->d_row_ptr; a.col_idx = mask->d_col_idx;
   a.col_ptr = mask->d_col_ptr; a.row_idx = mask->d_row_idx;
+  a.slice = mask->d_slice; a.max_slice = mask->max_slice;
   a.slice_t = mask->d_slice_t; a.max_slice_t = mask->max_slice_t;
   a.B = B; a.H = H; a.N = N; a.n_blocks = mask->n_blocks;
   a.scale = scale;

@@ -3,20 +3,23 @@
 //     P = exp(scale*Q K^T - LSE),  dV = P^T dO,  dP = dO V^T,  delta = rowsum(dO * O),
 //     dS = P * (dP - delta),       dQ = scale * dS K,          dK = scale * dS^T Q.
 //
-// Three kernels:
-//   prepare : delta[b,h,q] = sum_d dO*O, and zero the fp32 dQ accumulator;
-//   main    : one workgroup per (batch, head, key block) walks the transposed list (the query
+// Three kernels, no atomics (results are reproducible run to run):
+//   prepare : delta[b,h,q] = sum_d dO*O;
+//   dkdv    : one workgroup per (batch, head, key block) walks the transposed list (the query
 //             blocks that list this key block) in stages of 64 query rows.  Wave w owns 32
 //             keys; its K and V rows stay in registers, dK^T and dV^T accumulate in registers
 //             (column = key = lane%32).  S and dP are computed with query rows as MFMA rows
 //             so that P and dS come out with keys across lanes: 8 accumulator rows at a time
 //             they are the B operands of dV^T += dO^T P and dK^T += Q^T dS, whose A operands
-//             are transposing LDS reads of the dO and Q stage tiles.  dS is also parked in
-//             LDS (key-major) so that, after a barrier, the waves split dQ = dS K of the stage
-//             by output tile and add it to the fp32 accumulator with atomics;
-//   finish  : dQ accumulator -> bf16.
-// Q and dO stage tiles, LSE and delta are copied HBM -> LDS by global_load_lds, double
-// buffered, one stage ahead.
+//             are transposing LDS reads of the dO and Q stage tiles;
+//   dq      : one workgroup per (batch, head, query block) walks the row list in stages of 64
+//             keys, like the forward kernel: wave w owns 32 query rows whose Q and dO rows stay
+//             in registers; S^T = K Q^T and dP^T = V dO^T come out with queries across lanes,
+//             LSE and delta are per-lane scalars, and dS^T feeds dQ^T += K^T dS^T from registers
+//             (A operand: transposing LDS reads of the K stage tile).  S and dP are recomputed
+//             here (7 products in total instead of 5), which is cheaper than pushing every
+//             listed pair's 64 KiB of dQ partial sums through memory atomics.
+// Stage tiles are copied HBM -> LDS by global_load_lds, double buffered, one stage ahead.
 #include "radial_internal.h"
 #include "radial_tile.h"
 
@@ -33,15 +36,11 @@ struct BwdTile {
   static constexpr int kSubs = BLK / kStageQ;  // stages per listed query block
   static constexpr int kSteps = D / 16;
   static constexpr int kDTiles = D / 32;
-  static constexpr int kKBytes = BLK * D * 2;            // K tile, key-major (read transposed for dQ)
   static constexpr int kQBytes = kStageQ * D * 2;        // Q or dO stage tile
   static constexpr int kStatBytes = 2 * kStageQ * 4;     // LSE and delta of a stage
   static constexpr int kStageBytes = 2 * kQBytes + kStatBytes;
-  static constexpr int kDsBytes = BLK * kStageQ * 2;     // dS^T tile [key][64 q]
-  static constexpr int kLdsBytes = kKBytes + 2 * kStageBytes + kDsBytes;
-  static constexpr int kKLoadsPerWave = kKBytes / 1024 / kWaves;
+  static constexpr int kLdsBytes = 2 * kStageBytes;
   static constexpr int kQLoadsPerWave = kQBytes / 1024 / kWaves;
-  static constexpr int kDqTilesPerWave = 2 * kDTiles / kWaves;  // 32x32 dQ tiles per wave per stage
 };
 
 template <int D>
@@ -62,40 +61,17 @@ __global__ void __launch_bounds__(256) bwd_prepare_kernel(const BwdArgs a) {
     const bf16x8 gv = *(const bf16x8*)g;
 #pragma unroll
     for (int i = 0; i < 8; ++i) sum += (float)ov[i] * (float)gv[i];
-    f32x4* acc = (f32x4*)(a.dq_acc + row * D + piece * 8);
-    acc[0] = f32x4{0.f, 0.f, 0.f, 0.f};
-    acc[1] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 #pragma unroll
   for (int off = kLanesPerRow / 2; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
   if (row < rows && piece == 0) a.delta[row] = sum;
 }
 
-template <int D>
-__global__ void __launch_bounds__(256) bwd_finish_kernel(const BwdArgs a) {
-  constexpr int kLanesPerRow = D / 8;
-  const int64_t rows = (int64_t)a.B * a.H * a.N;
-  const int64_t row = (int64_t)blockIdx.x * (256 / kLanesPerRow) + threadIdx.x / kLanesPerRow;
-  const int piece = threadIdx.x % kLanesPerRow;
-  if (row >= rows) return;
-  const int32_t q = (int32_t)(row % a.N);
-  const int32_t bh = (int32_t)(row / a.N);
-  const int32_t b = bh / a.H, h = bh % a.H;
-  const f32x4* acc = (const f32x4*)(a.dq_acc + row * D + piece * 8);
-  const f32x4 x = acc[0], y = acc[1];
-  u32x4 w = {pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3]), pack_bf16(y[0], y[1]), pack_bf16(y[2], y[3])};
-  __bf16* dst = (__bf16*)a.dq.ptr + (int64_t)b * a.dq.sb + (int64_t)h * a.dq.sh + (int64_t)q * a.dq.sn + piece * 8;
-  *(u32x4*)dst = w;
-}
-
 template <int D, int BLK>
-__global__ void __launch_bounds__(2 * BLK, 1) radial_bwd_kernel(const BwdArgs a) {
+__global__ void __launch_bounds__(2 * BLK, 1) radial_bwd_dkdv_kernel(const BwdArgs a) {
   using T = BwdTile<D, BLK>;
-  using QT = SwzTile<D>;         // K, Q, dO tiles: rows of D elements
-  using ST = SwzTile<kStageQ>;   // dS^T tile: rows of 64 query positions
+  using QT = SwzTile<D>;  // Q, dO tiles: rows of D elements
   extern __shared__ __attribute__((aligned(1024))) char lds[];
-  char* const lds_kt = lds;
-  char* const lds_ds = lds + T::kKBytes + 2 * T::kStageBytes;
   const uint32_t lds_base = lds_address(lds);
 
   const int lane = threadIdx.x & 63;
@@ -121,7 +97,6 @@ __global__ void __launch_bounds__(2 * BLK, 1) radial_bwd_kernel(const BwdArgs a)
   const __bf16* gp = (const __bf16*)a.dout.ptr + (int64_t)b * a.dout.sb + (int64_t)h * a.dout.sh;
   const float* lsep = a.lse + (int64_t)bh * a.N;
   const float* deltap = a.delta + (int64_t)bh * a.N;
-  float* dqp = a.dq_acc + (int64_t)bh * a.N * D;
 
   const int32_t list_lo = __builtin_amdgcn_readfirstlane(a.col_ptr[kb]);
   const int32_t n_list = __builtin_amdgcn_readfirstlane(a.col_ptr[kb + 1]) - list_lo;
@@ -144,17 +119,6 @@ __global__ void __launch_bounds__(2 * BLK, 1) radial_bwd_kernel(const BwdArgs a)
     }
   }
 
-  // the K tile, key-major, for the transposing reads of the dQ product
-#pragma unroll
-  for (int i = 0; i < T::kKLoadsPerWave; ++i) {
-    const int chunk = wave * T::kKLoadsPerWave + i;
-    int r, c;
-    QT::source_of(chunk * 64 + lane, r, c);
-    int32_t row = kb * BLK + r;
-    row = row < a.N ? row : a.N - 1;
-    copy16_to_lds(kp + (int64_t)row * a.k.sn + c, lds_base + chunk * 1024);
-  }
-
   const int32_t* rows_list = a.row_idx + list_lo;
   int32_t cvec = lane < n_list ? rows_list[lane] : 0;
   int32_t nvec = 64 + lane < n_list ? rows_list[64 + lane] : 0;
@@ -165,7 +129,7 @@ __global__ void __launch_bounds__(2 * BLK, 1) radial_bwd_kernel(const BwdArgs a)
 
   // Copies Q, dO (64 rows from q0) and their LSE / delta into stage buffer `buf`.
   auto issue_stage = [&](int32_t q0, int buf) {
-    const uint32_t qdst = lds_base + T::kKBytes + buf * T::kStageBytes + wave * T::kQLoadsPerWave * 1024;
+    const uint32_t qdst = lds_base + buf * T::kStageBytes + wave * T::kQLoadsPerWave * 1024;
     const uint32_t gdst = qdst + T::kQBytes;
 #pragma unroll
     for (int i = 0; i < T::kQLoadsPerWave; ++i) {
@@ -177,7 +141,7 @@ __global__ void __launch_bounds__(2 * BLK, 1) radial_bwd_kernel(const BwdArgs a)
     if (wave < 2) {
       int32_t r = q0 + lane;
       r = r < a.N ? r : a.N - 1;
-      const uint32_t sdst = lds_base + T::kKBytes + buf * T::kStageBytes + 2 * T::kQBytes + wave * kStageQ * 4;
+      const uint32_t sdst = lds_base + buf * T::kStageBytes + 2 * T::kQBytes + wave * kStageQ * 4;
       copy4_to_lds((wave == 0 ? lsep : deltap) + r, sdst);
     }
   };
@@ -208,11 +172,11 @@ __global__ void __launch_bounds__(2 * BLK, 1) radial_bwd_kernel(const BwdArgs a)
       q0_next = __builtin_amdgcn_readlane(cvec, e1 & 63) * BLK + ((u + 1) % T::kSubs) * kStageQ;
     }
 
-    wait_all_copies();  // stage u (and, the first time, the K tile) has landed
-    __syncthreads();    // for every wave; stage u-1 including its dQ phase is finished
+    wait_all_copies();  // stage u has landed
+    __syncthreads();    // for every wave; stage u-1 is finished
     if (has_next) issue_stage(q0_next, buf ^ 1);
 
-    const char* sq = lds + T::kKBytes + buf * T::kStageBytes;
+    const char* sq = lds + buf * T::kStageBytes;
     const char* sg = sq + T::kQBytes;
     const char* st = sg + T::kQBytes;  // 64 x LSE then 64 x delta
     const bool ragged_q = q0 + kStageQ > a.N;
@@ -248,8 +212,6 @@ __global__ void __launch_bounds__(2 * BLK, 1) radial_bwd_kernel(const BwdArgs a)
         pp[2 * e4 + 1] = pack_bf16(p[2], p[3]);
         dsp[2 * e4] = pack_bf16(ds[0], ds[1]);
         dsp[2 * e4 + 1] = pack_bf16(ds[2], ds[3]);
-        // park dS^T[key][q]: 4 consecutive query positions
-        *lds_cast<u32x2>(lds_ds + ST::elem(wave * 32 + lq, ql)) = u32x2{dsp[2 * e4], dsp[2 * e4 + 1]};
       }
       // dV^T[d, key] += dO^T[d, q] P[q, key];  dK^T[d, key] += Q^T[d, q] dS[q, key]
 #pragma unroll
@@ -267,37 +229,10 @@ __global__ void __launch_bounds__(2 * BLK, 1) radial_bwd_kernel(const BwdArgs a)
         }
       }
     }
-    __syncthreads();  // dS^T of all keys of the block is in LDS
-
-    // dQ[q, d] += scale * dS[q, :] K[:, d]: this wave's share of the 2 x kDTiles output tiles
-#pragma unroll
-    for (int j = 0; j < T::kDqTilesPerWave; ++j) {
-      const int ti = wave * T::kDqTilesPerWave + j;
-      const int qt = ti / T::kDTiles, dt = ti % T::kDTiles;
-      f32x16 acc;
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-#pragma unroll
-      for (int t3 = 0; t3 < BLK / 16; ++t3) {
-        const int kr = 16 * t3 + 4 * g + (i16 >> 2);  // key row of the first 4-key patch
-        const int qc = qt * 32 + 16 * half16 + 4 * (i16 & 3);
-        const int dc = 32 * dt + 16 * half16 + 4 * (i16 & 3);
-        const u32x2 a0 = lds_read_tr(lds_ds + ST::elem(kr, qc)), a1 = lds_read_tr(lds_ds + ST::elem(kr + 8, qc));
-        const u32x2 b0 = lds_read_tr(lds_kt + QT::elem(kr, dc)), b1 = lds_read_tr(lds_kt + QT::elem(kr + 8, dc));
-        acc = mfma32(as_bf16x8(a0[0], a0[1], a1[0], a1[1]), as_bf16x8(b0[0], b0[1], b1[0], b1[1]), acc);
-      }
-      // acc element e: query q0 + 32qt + 8(e/4) + 4g + e%4, column d = 32dt + lq
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int32_t q = q0 + qt * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
-        if (q < a.N) unsafeAtomicAdd(dqp + (int64_t)q * D + 32 * dt + lq, acc[e] * a.scale);
-      }
-    }
     q0 = q0_next;
   }
 
   // ---- epilogue: dK = scale * dK^T, dV -----------------------------------------------------
-  if (n_stage == 0) wait_all_copies();  // nothing may stay in flight when the wave ends
   if (key_ok) {
     __bf16* dkd = (__bf16*)a.dk.ptr + (int64_t)b * a.dk.sb + (int64_t)h * a.dk.sh + (int64_t)key_row * a.dk.sn;
     __bf16* dvd = (__bf16*)a.dv.ptr + (int64_t)b * a.dv.sb + (int64_t)h * a.dv.sh + (int64_t)key_row * a.dv.sn;
@@ -314,23 +249,211 @@ __global__ void __launch_bounds__(2 * BLK, 1) radial_bwd_kernel(const BwdArgs a)
   }
 }
 
+constexpr int kStageKeys = 64;  // keys per stage of the dQ kernel
+
+template <int D, int BLK>
+struct DqTile {
+  static constexpr int kWaves = BLK / 32;  // one wave per 32 query rows
+  static constexpr int kThreads = 64 * kWaves;
+  static constexpr int kSubs = BLK / kStageKeys;
+  static constexpr int kSteps = D / 16;
+  static constexpr int kDTiles = D / 32;
+  static constexpr int kTileBytes = kStageKeys * D * 2;  // one K (or V) stage tile
+  static constexpr int kLoadsPerWave = kTileBytes / 1024 / kWaves;
+};
+
+template <int D, int BLK>
+__global__ void __launch_bounds__(2 * BLK, 2) radial_bwd_dq_kernel(const BwdArgs a) {
+  using T = DqTile<D, BLK>;
+  using SW = SwzTile<D>;
+  // [stage buffer][K, V][64 x D bf16]
+  __shared__ __attribute__((aligned(1024))) char lds[4 * T::kTileBytes];
+  const uint32_t lds_base = lds_address(lds);
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lq = lane & 31;
+  const int g = lane >> 5;
+  const int i16 = lane & 15;
+  const int half16 = (lane >> 4) & 1;
+
+  // work item: XCD x owns the query blocks [slice[x], slice[x+1]) of every (batch, head)
+  const int32_t xcd = blockIdx.x & 7;
+  const int32_t s0 = a.slice[xcd];
+  const int32_t slice_len = a.slice[xcd + 1] - s0;
+  const int64_t idx = blockIdx.x >> 3;
+  if (slice_len <= 0 || idx >= (int64_t)slice_len * a.B * a.H) return;
+  const int32_t bh = (int32_t)(idx / slice_len);
+  const int32_t qb = s0 + (int32_t)(idx % slice_len);
+  const int32_t b = bh / a.H, h = bh % a.H;
+
+  const __bf16* qp = (const __bf16*)a.q.ptr + (int64_t)b * a.q.sb + (int64_t)h * a.q.sh;
+  const __bf16* kp = (const __bf16*)a.k.ptr + (int64_t)b * a.k.sb + (int64_t)h * a.k.sh;
+  const __bf16* vp = (const __bf16*)a.v.ptr + (int64_t)b * a.v.sb + (int64_t)h * a.v.sh;
+  const __bf16* gp = (const __bf16*)a.dout.ptr + (int64_t)b * a.dout.sb + (int64_t)h * a.dout.sh;
+
+  const int32_t list_lo = __builtin_amdgcn_readfirstlane(a.row_ptr[qb]);
+  const int32_t n_list = __builtin_amdgcn_readfirstlane(a.row_ptr[qb + 1]) - list_lo;
+  const int32_t n_stage = n_list * T::kSubs;
+  const int32_t q_row = qb * BLK + wave * 32 + lq;
+  const bool q_ok = q_row < a.N;
+  const int64_t q_clamped = q_ok ? q_row : a.N - 1;
+
+  // Q and dO rows of this lane's query: B operands of S^T = K Q^T and dP^T = V dO^T.
+  bf16x8 qf[T::kSteps], gf[T::kSteps];
+  {
+    const __bf16* qs = qp + q_clamped * a.q.sn + 8 * g;
+    const __bf16* gs = gp + q_clamped * a.dout.sn + 8 * g;
+#pragma unroll
+    for (int t = 0; t < T::kSteps; ++t) {
+      qf[t] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qs + 16 * t));
+      gf[t] = __builtin_bit_cast(bf16x8, *(const u32x4*)(gs + 16 * t));
+    }
+  }
+  const float lse2 = a.lse[(int64_t)bh * a.N + q_clamped] * kLog2e;  // rows past N: values unused
+  const float dlt = a.delta[(int64_t)bh * a.N + q_clamped];
+
+  const int32_t* cols = a.col_idx + list_lo;
+  int32_t cvec = lane < n_list ? cols[lane] : 0;
+  int32_t nvec = 64 + lane < n_list ? cols[64 + lane] : 0;
+
+  uint32_t koff[T::kLoadsPerWave], voff[T::kLoadsPerWave];
+#pragma unroll
+  for (int i = 0; i < T::kLoadsPerWave; ++i) {
+    int r, col;
+    SW::source_of((wave * T::kLoadsPerWave + i) * 64 + lane, r, col);
+    koff[i] = (uint32_t)(r * (int32_t)a.k.sn + col) * 2u;
+    voff[i] = (uint32_t)(r * (int32_t)a.v.sn + col) * 2u;
+  }
+  // Copies the 64 K rows and V rows starting at key `key0` into stage buffer `buf`; rows past
+  // N-1 are clamped to N-1 (their P is forced to zero).
+  auto issue_stage = [&](int32_t key0, int buf) {
+    const uint32_t kdst = lds_base + buf * 2 * T::kTileBytes + wave * T::kLoadsPerWave * 1024;
+    const uint32_t vdst = kdst + T::kTileBytes;
+    if (key0 + kStageKeys <= a.N) {
+      const __bf16* kbase = kp + (int64_t)key0 * a.k.sn;  // wave-uniform
+      const __bf16* vbase = vp + (int64_t)key0 * a.v.sn;
+#pragma unroll
+      for (int i = 0; i < T::kLoadsPerWave; ++i) copy16_to_lds_sv(kbase, koff[i], kdst + i * 1024);
+#pragma unroll
+      for (int i = 0; i < T::kLoadsPerWave; ++i) copy16_to_lds_sv(vbase, voff[i], vdst + i * 1024);
+    } else {
+      const int32_t last = a.N - 1 - key0;  // a stage wholly past N reads row N-1 only
+#pragma unroll
+      for (int i = 0; i < T::kLoadsPerWave; ++i) {
+        int r, col;
+        SW::source_of((wave * T::kLoadsPerWave + i) * 64 + lane, r, col);
+        r = r < last ? r : last;
+        copy16_to_lds(kp + ((int64_t)key0 + r) * a.k.sn + col, kdst + i * 1024);
+        copy16_to_lds(vp + ((int64_t)key0 + r) * a.v.sn + col, vdst + i * 1024);
+      }
+    }
+  };
+
+  f32x16 dq[T::kDTiles];  // dQ^T: column = this lane's query, rows = d
+#pragma unroll
+  for (int i = 0; i < T::kDTiles; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) dq[i][e] = 0.f;
+  const float c = a.scale * kLog2e;
+
+  int32_t key0 = 0;
+  if (n_stage > 0) {
+    key0 = __builtin_amdgcn_readlane(cvec, 0) * BLK;
+    issue_stage(key0, 0);
+  }
+  for (int32_t u = 0; u < n_stage; ++u) {
+    const int buf = u & 1;
+    int32_t key0_next = 0;
+    const bool has_next = u + 1 < n_stage;
+    if (has_next) {
+      const int32_t e1 = (u + 1) / T::kSubs;
+      if ((u + 1) % T::kSubs == 0 && (e1 & 63) == 0) {
+        cvec = nvec;
+        nvec = e1 + 64 + lane < n_list ? cols[e1 + 64 + lane] : 0;
+      }
+      key0_next = __builtin_amdgcn_readlane(cvec, e1 & 63) * BLK + ((u + 1) % T::kSubs) * kStageKeys;
+    }
+    wait_all_copies();
+    __syncthreads();
+    if (has_next) issue_stage(key0_next, buf ^ 1);
+
+    const char* lds_k = lds + buf * 2 * T::kTileBytes;
+    const char* lds_v = lds_k + T::kTileBytes;
+    const bool ragged = key0 + kStageKeys > a.N;
+#pragma unroll
+    for (int kt = 0; kt < kStageKeys / 32; ++kt) {
+      // S^T[key, q] and dP^T[key, q] for 32 keys x this wave's 32 queries
+      f32x16 s, dp;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) s[e] = dp[e] = 0.f;
+#pragma unroll
+      for (int t = 0; t < T::kSteps; ++t) {
+        const bf16x8 kfrag = *lds_cast<const bf16x8>(lds_k + SW::piece(kt * 32 + lq, 2 * t + g));
+        const bf16x8 vfrag = *lds_cast<const bf16x8>(lds_v + SW::piece(kt * 32 + lq, 2 * t + g));
+        s = mfma32(kfrag, qf[t], s);
+        dp = mfma32(vfrag, gf[t], dp);
+      }
+      // element e: key = key0 + 32kt + 8(e/4) + 4g + e%4, query = q_row (this lane)
+      uint32_t dsp[8];
+#pragma unroll
+      for (int e = 0; e < 16; e += 2) {
+        float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], c, -lse2));
+        float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e + 1], c, -lse2));
+        if (ragged) {
+          const int32_t key = key0 + kt * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
+          if (key >= a.N) p0 = 0.f;
+          if (key + 1 >= a.N) p1 = 0.f;
+        }
+        dsp[e >> 1] = pack_bf16(p0 * (dp[e] - dlt), p1 * (dp[e + 1] - dlt));
+      }
+      // dQ^T[d, q] += K^T[d, key] dS^T[key, q]
+#pragma unroll
+      for (int t2 = 0; t2 < 2; ++t2) {
+        const bf16x8 dsf = as_bf16x8(dsp[4 * t2], dsp[4 * t2 + 1], dsp[4 * t2 + 2], dsp[4 * t2 + 3]);
+        const int r0 = kt * 32 + 16 * t2 + 4 * g + (i16 >> 2);
+#pragma unroll
+        for (int dt = 0; dt < T::kDTiles; ++dt) {
+          const int col = 32 * dt + 16 * half16 + 4 * (i16 & 3);
+          const u32x2 k0 = lds_read_tr(lds_k + SW::elem(r0, col)), k1 = lds_read_tr(lds_k + SW::elem(r0 + 8, col));
+          dq[dt] = mfma32(as_bf16x8(k0[0], k0[1], k1[0], k1[1]), dsf, dq[dt]);
+        }
+      }
+    }
+    key0 = key0_next;
+  }
+
+  if (q_ok) {
+    __bf16* dst = (__bf16*)a.dq.ptr + (int64_t)b * a.dq.sb + (int64_t)h * a.dq.sh + (int64_t)q_row * a.dq.sn;
+#pragma unroll
+    for (int dt = 0; dt < T::kDTiles; ++dt)
+#pragma unroll
+      for (int e4 = 0; e4 < 4; ++e4)  // dq[dt][4*e4 + x] is d = 32dt + 8*e4 + 4g + x
+        *(u32x2*)(dst + 32 * dt + 8 * e4 + 4 * g) =
+            u32x2{pack_bf16(dq[dt][4 * e4] * a.scale, dq[dt][4 * e4 + 1] * a.scale),
+                  pack_bf16(dq[dt][4 * e4 + 2] * a.scale, dq[dt][4 * e4 + 3] * a.scale)};
+  }
+}
+
 template <int D, int BLK>
 int launch(const BwdArgs& a, hipStream_t stream) {
   using T = BwdTile<D, BLK>;
   const int64_t rows = (int64_t)a.B * a.H * a.N;
   const int rows_per_block = 256 / (D / 8);
   const int64_t prep_grid = (rows + rows_per_block - 1) / rows_per_block;
-  const int64_t grid = 8LL * a.B * a.H * a.max_slice_t;
-  if (prep_grid > 0x7fffffffLL || grid > 0x7fffffffLL) return fail(RADIAL_ESHAPE, "problem too large for one launch");
+  const int64_t grid_kv = 8LL * a.B * a.H * a.max_slice_t;
+  const int64_t grid_q = 8LL * a.B * a.H * a.max_slice;
+  if (prep_grid > 0x7fffffffLL || grid_kv > 0x7fffffffLL || grid_q > 0x7fffffffLL)
+    return fail(RADIAL_ESHAPE, "problem too large for one launch");
   static bool configured = false;  // per template instance
   if (!configured) {
-    RADIAL_HIP_TRY(hipFuncSetAttribute((const void*)radial_bwd_kernel<D, BLK>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       T::kLdsBytes));
+    RADIAL_HIP_TRY(hipFuncSetAttribute((const void*)radial_bwd_dkdv_kernel<D, BLK>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsBytes));
     configured = true;
   }
   bwd_prepare_kernel<D><<<dim3((unsigned)prep_grid), dim3(256), 0, stream>>>(a);
-  if (grid > 0) radial_bwd_kernel<D, BLK><<<dim3((unsigned)grid), dim3(T::kThreads), T::kLdsBytes, stream>>>(a);
-  bwd_finish_kernel<D><<<dim3((unsigned)prep_grid), dim3(256), 0, stream>>>(a);
+  if (grid_kv > 0) radial_bwd_dkdv_kernel<D, BLK><<<dim3((unsigned)grid_kv), dim3(T::kThreads), T::kLdsBytes, stream>>>(a);
+  if (grid_q > 0) radial_bwd_dq_kernel<D, BLK><<<dim3((unsigned)grid_q), dim3(DqTile<D, BLK>::kThreads), 0, stream>>>(a);
   RADIAL_HIP_TRY(hipGetLastError());
   return RADIAL_OK;
 }

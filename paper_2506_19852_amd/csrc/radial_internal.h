@@ -61,13 +61,13 @@ struct BwdArgs {
   TensorArg q, k, v, o, dout, dq, dk, dv;
   const float* lse;
   float* delta;   // workspace: [B, H, N] rowsum(dO * O)
-  float* dq_acc;  // workspace: [B, H, N, D] fp32 accumulator for dQ
   const int32_t* row_ptr;
   const int32_t* col_idx;
   const int32_t* col_ptr;
   const int32_t* row_idx;
+  const int32_t* slice;    // [9] query-block partition over the XCDs
   const int32_t* slice_t;  // [9] key-block partition over the XCDs
-  int32_t max_slice_t;
+  int32_t max_slice, max_slice_t;
   int32_t B, H, N, n_blocks;
   float scale;
 };

@@ -49,7 +49,12 @@ __device__ __forceinline__ bf16x8 as_bf16x8(uint32_t a, uint32_t b, uint32_t c, 
 __device__ __forceinline__ void copy16_to_lds(const void* gptr, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory");
 }
-// Same with 4 bytes per lane (256 bytes per wave).
+// copy16_to_lds with the address split into a wave-uniform 64-bit base (SGPRs) and a per-lane
+// 32-bit byte offset, so that walking to the next tile costs scalar arithmetic only.
+__device__ __forceinline__ void copy16_to_lds_sv(const void* base, uint32_t byte_offset, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(byte_offset), "s"(base) : "memory");
+}
+// Same as copy16_to_lds with 4 bytes per lane (256 bytes per wave).
 __device__ __forceinline__ void copy4_to_lds(const void* gptr, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_addr), "v"(gptr) : "memory");
 }
