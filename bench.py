@@ -78,6 +78,8 @@ def main():
     ap.add_argument("--workload", default="cfg3_hunyuan720p")
     ap.add_argument("--dense-steps", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--token-exact", action="store_true",
+                    help="apply the token-level rule inside the listed blocks (same blocks computed; default: block-dense)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain device copy of q (known size) so a rocprofv3 --pmc run can scale FETCH_SIZE/WRITE_SIZE")
     args = ap.parse_args()
@@ -95,6 +97,8 @@ def main():
     torch.cuda.set_device(0)
     x = wl.make_inputs(w, dev)
     flags = rb.RADIAL_MASK_TRANSPOSE if w.backward else 0
+    if args.token_exact:
+        flags |= rb.RADIAL_MASK_TOKEN_EXACT
     out = torch.empty_like(x["q"])
     lse = torch.empty((w.B, w.H, w.N), dtype=torch.float32, device=dev)
     grads = ws = None
@@ -163,7 +167,8 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "D": w.D, "frames": w.frames,
                    "tokens_per_frame": w.tokens_per_frame, "block": w.block, "sink_frames": 1,
-                   "listed_block_pairs": int(row_ptr[-1]), "pass": "fwd+bwd" if w.backward else "fwd"},
+                   "listed_block_pairs": int(row_ptr[-1]), "pass": "fwd+bwd" if w.backward else "fwd",
+                   "inside_listed_blocks": "token rule" if args.token_exact else "dense"},
         "fwd_kernel_ms": round(kernel_ms, 3),
         "dense_fwd_kernel_ms": round(dense_ms, 3),
         "dense_tflops": round(dense_flops / (dense_ms * 1e-3) / 1e12, 2),

@@ -66,6 +66,10 @@ typedef struct {
 } radial_mask_params;
 
 #define RADIAL_MASK_TRANSPOSE 1u /* also build the per-key-block list of query blocks (needed by bwd) */
+/* radial_mask_build only: attention calls with this mask apply the token-level rule above
+ * inside the listed blocks as well, i.e. they evaluate Eq. 2 under the token mask of Sec. 4.2
+ * itself instead of its block cover.  Needs tokens_per_frame >= 64 (EUNSUPPORTED otherwise). */
+#define RADIAL_MASK_TOKEN_EXACT 2u
 
 /* Opaque.  Owns device copies of row_ptr[nqb+1], col_idx[nnz] (and the transposed lists when
  * requested) plus a launch order for the attention kernels.  Immutable after construction;
@@ -121,9 +125,9 @@ typedef struct {
  *   lse     : device float [B, H, N] contiguous, receives log(sum_k exp(scale * q.k)) over the
  *             visible keys of each row (needed by radial_attn_bwd), or NULL;
  *   scale   : the 1/sqrt(d) of Eq. 2 (any positive finite value is accepted).
- * Inside a listed block pair every key with index < N is visible.  A query row whose block
- * lists nothing gets out = 0 and lse = -inf.  Products run on bf16 MFMA with fp32
- * accumulation; the softmax is fp32; P is rounded to bf16 before P.V; out is rounded to
+ * Inside a listed block pair every key with index < N is visible; with a mask built under
+ * RADIAL_MASK_TOKEN_EXACT only the pairs the token rule allows are.  A query row with no
+ * visible key gets out = 0 and lse = -inf.  Products run on bf16 MFMA with fp32 accumulation; the softmax is fp32; P is rounded to bf16 before P.V; out is rounded to
  * nearest-even bf16.  Allocates nothing.
  * Errors: EINVAL (NULL, scale), EUNSUPPORTED (D not 64/128), ESHAPE (N != mask n_tokens,
  * misaligned pointer/stride, B*H*n_blocks >= 2^31), EHIP. */

@@ -13,6 +13,7 @@ import numpy as np
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libradial.so")
 
 RADIAL_MASK_TRANSPOSE = 1
+RADIAL_MASK_TOKEN_EXACT = 2
 STATUS = {0: "RADIAL_OK", -1: "RADIAL_EINVAL", -2: "RADIAL_ENOMEM", -3: "RADIAL_EHIP",
           -4: "RADIAL_EUNSUPPORTED", -5: "RADIAL_ESHAPE"}
 

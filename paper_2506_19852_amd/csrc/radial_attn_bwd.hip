@@ -67,7 +67,8 @@ __global__ void __launch_bounds__(256) bwd_prepare_kernel(const BwdArgs a) {
   if (row < rows && piece == 0) a.delta[row] = sum;
 }
 
-template <int D, int BLK>
+// kExact (all three kernels' callers): apply the token-level rule inside the listed blocks.
+template <int D, int BLK, bool kExact>
 __global__ void __launch_bounds__(2 * BLK, 1) radial_bwd_dkdv_kernel(const BwdArgs a) {
   using T = BwdTile<D, BLK>;
   using QT = SwzTile<D>;  // Q, dO tiles: rows of D elements
@@ -122,6 +123,12 @@ __global__ void __launch_bounds__(2 * BLK, 1) radial_bwd_dkdv_kernel(const BwdAr
   const int32_t* rows_list = a.row_idx + list_lo;
   int32_t cvec = lane < n_list ? rows_list[lane] : 0;
   int32_t nvec = 64 + lane < n_list ? rows_list[64 + lane] : 0;
+  // token rule: (frame, position) of this lane's key and of every listed query block's first row
+  StagePos key_at = {0, 0}, cvec_at = {0, 0};
+  if (kExact) {
+    key_at = block_pos(key_ok ? key_row : a.N - 1, a.rule.s);
+    cvec_at = block_pos(cvec * BLK, a.rule.s);
+  }
 
   int32_t srow[T::kQLoadsPerWave], scol[T::kQLoadsPerWave];
 #pragma unroll
@@ -154,8 +161,10 @@ __global__ void __launch_bounds__(2 * BLK, 1) radial_bwd_dkdv_kernel(const BwdAr
   const float c = a.scale * kLog2e;
 
   int32_t q0 = 0;
+  StagePos q_at = {0, 0}, q_at_next = {0, 0};
   if (n_stage > 0) {
     q0 = __builtin_amdgcn_readlane(cvec, 0) * BLK;
+    if (kExact) q_at = stage_pos(cvec_at, 0, 0, a.rule.s);
     issue_stage(q0, 0);
   }
 
@@ -168,8 +177,10 @@ __global__ void __launch_bounds__(2 * BLK, 1) radial_bwd_dkdv_kernel(const BwdAr
       if ((u + 1) % T::kSubs == 0 && (e1 & 63) == 0) {
         cvec = nvec;
         nvec = e1 + 64 + lane < n_list ? rows_list[e1 + 64 + lane] : 0;
+        if (kExact) cvec_at = block_pos(cvec * BLK, a.rule.s);
       }
       q0_next = __builtin_amdgcn_readlane(cvec, e1 & 63) * BLK + ((u + 1) % T::kSubs) * kStageQ;
+      if (kExact) q_at_next = stage_pos(cvec_at, e1 & 63, ((u + 1) % T::kSubs) * kStageQ, a.rule.s);
     }
 
     wait_all_copies();  // stage u has landed
@@ -180,6 +191,15 @@ __global__ void __launch_bounds__(2 * BLK, 1) radial_bwd_dkdv_kernel(const BwdAr
     const char* sg = sq + T::kQBytes;
     const char* st = sg + T::kQBytes;  // 64 x LSE then 64 x delta
     const bool ragged_q = q0 + kStageQ > a.N;
+    StageRule vis = {};
+    if (kExact) {
+      vis = stage_rule(a.rule, key_at, q_at, false);  // which of the stage's queries see this lane's key
+      if (vis.none) {  // no pair of this wave's keys with the stage's queries
+        q0 = q0_next;
+        q_at = q_at_next;
+        continue;
+      }
+    }
 
 #pragma unroll
     for (int qt = 0; qt < 2; ++qt) {
@@ -195,6 +215,11 @@ __global__ void __launch_bounds__(2 * BLK, 1) radial_bwd_dkdv_kernel(const BwdAr
         dp = mfma32(gfrag, vf[t], dp);
       }
       // element e: key = key_row (this lane), query = q0 + 32qt + 8(e/4) + 4g + e%4
+      if (kExact && vis.partial) {  // hidden pairs: P = exp(-inf) = 0
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          if (!vis.visible(qt * 32 + 8 * (e >> 2) + 4 * g + (e & 3))) s[e] = -INFINITY;
+      }
       uint32_t pp[8], dsp[8];
 #pragma unroll
       for (int e4 = 0; e4 < 4; ++e4) {
@@ -230,6 +255,7 @@ __global__ void __launch_bounds__(2 * BLK, 1) radial_bwd_dkdv_kernel(const BwdAr
       }
     }
     q0 = q0_next;
+    q_at = q_at_next;
   }
 
   // ---- epilogue: dK = scale * dK^T, dV -----------------------------------------------------
@@ -262,7 +288,7 @@ struct DqTile {
   static constexpr int kLoadsPerWave = kTileBytes / 1024 / kWaves;
 };
 
-template <int D, int BLK>
+template <int D, int BLK, bool kExact>
 __global__ void __launch_bounds__(2 * BLK, 2) radial_bwd_dq_kernel(const BwdArgs a) {
   using T = DqTile<D, BLK>;
   using SW = SwzTile<D>;
@@ -316,6 +342,12 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_bwd_dq_kernel(const BwdArgs
   const int32_t* cols = a.col_idx + list_lo;
   int32_t cvec = lane < n_list ? cols[lane] : 0;
   int32_t nvec = 64 + lane < n_list ? cols[64 + lane] : 0;
+  // token rule: (frame, position) of this lane's query and of every listed key block's first key
+  StagePos q_at = {0, 0}, cvec_at = {0, 0};
+  if (kExact) {
+    q_at = block_pos((int32_t)q_clamped, a.rule.s);
+    cvec_at = block_pos(cvec * BLK, a.rule.s);
+  }
 
   uint32_t koff[T::kLoadsPerWave], voff[T::kLoadsPerWave];
 #pragma unroll
@@ -358,8 +390,10 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_bwd_dq_kernel(const BwdArgs
   const float c = a.scale * kLog2e;
 
   int32_t key0 = 0;
+  StagePos k_at = {0, 0}, k_at_next = {0, 0};
   if (n_stage > 0) {
     key0 = __builtin_amdgcn_readlane(cvec, 0) * BLK;
+    if (kExact) k_at = stage_pos(cvec_at, 0, 0, a.rule.s);
     issue_stage(key0, 0);
   }
   for (int32_t u = 0; u < n_stage; ++u) {
@@ -371,8 +405,10 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_bwd_dq_kernel(const BwdArgs
       if ((u + 1) % T::kSubs == 0 && (e1 & 63) == 0) {
         cvec = nvec;
         nvec = e1 + 64 + lane < n_list ? cols[e1 + 64 + lane] : 0;
+        if (kExact) cvec_at = block_pos(cvec * BLK, a.rule.s);
       }
       key0_next = __builtin_amdgcn_readlane(cvec, e1 & 63) * BLK + ((u + 1) % T::kSubs) * kStageKeys;
+      if (kExact) k_at_next = stage_pos(cvec_at, e1 & 63, ((u + 1) % T::kSubs) * kStageKeys, a.rule.s);
     }
     wait_all_copies();
     __syncthreads();
@@ -381,6 +417,15 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_bwd_dq_kernel(const BwdArgs
     const char* lds_k = lds + buf * 2 * T::kTileBytes;
     const char* lds_v = lds_k + T::kTileBytes;
     const bool ragged = key0 + kStageKeys > a.N;
+    StageRule vis = {};
+    if (kExact) {
+      vis = stage_rule(a.rule, q_at, k_at, true);  // which of the stage's keys this lane's query sees
+      if (vis.none) {  // no pair of this wave's queries with the stage's keys
+        key0 = key0_next;
+        k_at = k_at_next;
+        continue;
+      }
+    }
 #pragma unroll
     for (int kt = 0; kt < kStageKeys / 32; ++kt) {
       // S^T[key, q] and dP^T[key, q] for 32 keys x this wave's 32 queries
@@ -395,6 +440,11 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_bwd_dq_kernel(const BwdArgs
         dp = mfma32(vfrag, gf[t], dp);
       }
       // element e: key = key0 + 32kt + 8(e/4) + 4g + e%4, query = q_row (this lane)
+      if (kExact && vis.partial) {  // hidden pairs: P = exp(-inf) = 0
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          if (!vis.visible(kt * 32 + 8 * (e >> 2) + 4 * g + (e & 3))) s[e] = -INFINITY;
+      }
       uint32_t dsp[8];
 #pragma unroll
       for (int e = 0; e < 16; e += 2) {
@@ -421,6 +471,7 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_bwd_dq_kernel(const BwdArgs
       }
     }
     key0 = key0_next;
+    k_at = k_at_next;
   }
 
   if (q_ok) {
@@ -435,7 +486,7 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_bwd_dq_kernel(const BwdArgs
   }
 }
 
-template <int D, int BLK>
+template <int D, int BLK, bool kExact>
 int launch(const BwdArgs& a, hipStream_t stream) {
   using T = BwdTile<D, BLK>;
   const int64_t rows = (int64_t)a.B * a.H * a.N;
@@ -447,15 +498,22 @@ int launch(const BwdArgs& a, hipStream_t stream) {
     return fail(RADIAL_ESHAPE, "problem too large for one launch");
   static bool configured = false;  // per template instance
   if (!configured) {
-    RADIAL_HIP_TRY(hipFuncSetAttribute((const void*)radial_bwd_dkdv_kernel<D, BLK>,
+    RADIAL_HIP_TRY(hipFuncSetAttribute((const void*)radial_bwd_dkdv_kernel<D, BLK, kExact>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsBytes));
     configured = true;
   }
   bwd_prepare_kernel<D><<<dim3((unsigned)prep_grid), dim3(256), 0, stream>>>(a);
-  if (grid_kv > 0) radial_bwd_dkdv_kernel<D, BLK><<<dim3((unsigned)grid_kv), dim3(T::kThreads), T::kLdsBytes, stream>>>(a);
-  if (grid_q > 0) radial_bwd_dq_kernel<D, BLK><<<dim3((unsigned)grid_q), dim3(DqTile<D, BLK>::kThreads), 0, stream>>>(a);
+  if (grid_kv > 0)
+    radial_bwd_dkdv_kernel<D, BLK, kExact><<<dim3((unsigned)grid_kv), dim3(T::kThreads), T::kLdsBytes, stream>>>(a);
+  if (grid_q > 0)
+    radial_bwd_dq_kernel<D, BLK, kExact><<<dim3((unsigned)grid_q), dim3(DqTile<D, BLK>::kThreads), 0, stream>>>(a);
   RADIAL_HIP_TRY(hipGetLastError());
   return RADIAL_OK;
+}
+
+template <int D, int BLK>
+int launch(const BwdArgs& a, hipStream_t stream) {
+  return a.rule.exact ? launch<D, BLK, true>(a, stream) : launch<D, BLK, false>(a, stream);
 }
 
 }  // namespace

@@ -20,24 +20,10 @@
 // 16-byte pieces are XOR-swizzled inside 256-byte LDS lines so that the 128-bit K reads and
 // the 64-bit transposing V reads are bank-conflict free.
 #include "radial_internal.h"
+#include "radial_tile.h"
 
 namespace radial {
 namespace {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(2))) float f32x2;
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
-
-// Generic pointer into a __shared__ array -> LDS (address space 3) pointer.
-template <class T>
-__device__ __forceinline__ __attribute__((address_space(3))) T* lds_cast(const void* p) {
-  return (__attribute__((address_space(3))) T*)(p);
-}
 
 constexpr int kStageKeys = 64;  // keys per pipeline stage
 
@@ -69,30 +55,13 @@ __device__ __forceinline__ int piece_offset(int r, int p) {
   return (line << 8) + ((slot ^ swizzle_key<D, kIsV>(line)) << 4);
 }
 
-// One 1 KiB HBM -> LDS copy: lane i's 16 bytes land at LDS address lds_addr + 16*i.
-__device__ __forceinline__ void copy16_to_lds(const void* gptr, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory");
-}
-
-// Same copy with the address split into a wave-uniform 64-bit base (SGPRs) and a per-lane
-// 32-bit byte offset, so that walking to the next tile costs scalar arithmetic only.
-__device__ __forceinline__ void copy16_to_lds(const void* base, uint32_t byte_offset, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-               ::"s"(lds_addr), "v"(byte_offset), "s"(base) : "memory");
-}
-
-__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
-  f32x2 f = {a, b};
-  bf16x2 h = __builtin_convertvector(f, bf16x2);
-  return __builtin_bit_cast(uint32_t, h);
-}
-
-template <int D, int BLK>
+// kExact: apply the token-level rule of the radial mask inside the listed blocks.
+template <int D, int BLK, bool kExact>
 __global__ void __launch_bounds__(2 * BLK, 2) radial_fwd_kernel(const FwdArgs a) {
   using T = Tile<D, BLK>;
   // [stage buffer][K, V][kStageKeys x D bf16]
   __shared__ __attribute__((aligned(1024))) char lds[2 * 2 * T::kStageBytes];
-  const uint32_t lds_base = (uint32_t)(uintptr_t)lds_cast<char>(lds);
+  const uint32_t lds_base = lds_address(lds);
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -140,6 +109,13 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_fwd_kernel(const FwdArgs a)
   const int32_t* cols = a.col_idx + list_lo;
   int32_t cvec = lane < n_list ? cols[lane] : 0;
   int32_t nvec = 64 + lane < n_list ? cols[64 + lane] : 0;
+  // token rule: this lane's query as (frame, position), and the same for the first token of
+  // every listed key block (one division per lane per 64 entries)
+  StagePos q_at = {0, 0}, cvec_at = {0, 0};
+  if (kExact) {
+    q_at = block_pos(q_ok ? q_row : a.N - 1, a.rule.s);
+    cvec_at = block_pos(cvec * BLK, a.rule.s);
+  }
 
   // Which piece of a stage tile each of this lane's copies fetches (fixed for the kernel),
   // as a byte offset from the first row of the tile.
@@ -167,9 +143,9 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_fwd_kernel(const FwdArgs a)
     const __bf16* vbase = vp + (int64_t)key0 * a.v.sn;
     if (key0 + kStageKeys <= a.N) {
 #pragma unroll
-      for (int i = 0; i < T::kLoadsPerWave; ++i) copy16_to_lds(kbase, koff[i], kdst + i * 1024);
+      for (int i = 0; i < T::kLoadsPerWave; ++i) copy16_to_lds_sv(kbase, koff[i], kdst + i * 1024);
 #pragma unroll
-      for (int i = 0; i < T::kLoadsPerWave; ++i) copy16_to_lds(vbase, voff[i], vdst + i * 1024);
+      for (int i = 0; i < T::kLoadsPerWave; ++i) copy16_to_lds_sv(vbase, voff[i], vdst + i * 1024);
     } else {  // ragged end of the sequence
       const int32_t last = a.N - 1 - key0;  // >= 0: a listed block starts below N; a stage past N reads row N-1
 #pragma unroll
@@ -195,8 +171,10 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_fwd_kernel(const FwdArgs a)
   const float c = a.scale * 1.4426950408889634f;  // exp(scale*x) = exp2(c*x)
 
   int32_t key0 = 0;  // first key of the stage about to be computed
+  StagePos k_at = {0, 0}, k_at_next = {0, 0};  // its (frame, position), and the next stage's
   if (n_stage > 0) {
     key0 = __builtin_amdgcn_readlane(cvec, 0) * BLK;
+    if (kExact) k_at = stage_pos(cvec_at, 0, 0, a.rule.s);
     issue_stage(key0, 0);
   }
 
@@ -210,14 +188,25 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_fwd_kernel(const FwdArgs a)
       if ((u + 1) % T::kSubs == 0 && (e1 & 63) == 0) {  // entering the next chunk of the list
         cvec = nvec;
         nvec = e1 + 64 + lane < n_list ? cols[e1 + 64 + lane] : 0;
+        if (kExact) cvec_at = block_pos(cvec * BLK, a.rule.s);
       }
       key0_next = __builtin_amdgcn_readlane(cvec, e1 & 63) * BLK + ((u + 1) % T::kSubs) * kStageKeys;
+      if (kExact) k_at_next = stage_pos(cvec_at, e1 & 63, ((u + 1) % T::kSubs) * kStageKeys, a.rule.s);
     }
 
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's copies of stage u have landed
     __syncthreads();                                  // ... and everyone's; stage u-1 is fully consumed
     if (has_next) issue_stage(key0_next, buf ^ 1);
 
+    StageRule vis = {};
+    if (kExact) {
+      vis = stage_rule(a.rule, q_at, k_at, true);
+      if (vis.none) {  // nothing in this stage for any row of this wave
+        key0 = key0_next;
+        k_at = k_at_next;
+        continue;
+      }
+    }
     const char* lds_k = lds + buf * 2 * T::kStageBytes;
     const char* lds_v = lds_k + T::kStageBytes;
 
@@ -245,15 +234,21 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_fwd_kernel(const FwdArgs a)
           if (key >= a.N) s[kt][e] = -INFINITY;
         }
     }
+    if (kExact) {  // keys the token rule hides from this lane's query
+      if (vis.partial) {
+#pragma unroll
+        for (int kt = 0; kt < T::kKeyTiles; ++kt)
+#pragma unroll
+          for (int e = 0; e < 16; ++e)
+            if (!vis.visible(kt * 32 + 8 * (e >> 2) + 4 * g + (e & 3))) s[kt][e] = -INFINITY;
+      }
+    }
     float mx = s[0][0];
 #pragma unroll
     for (int kt = 0; kt < T::kKeyTiles; ++kt)
 #pragma unroll
       for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[kt][e]);
-    {  // exchange with lane^32 (the other half of the row's keys) without going through LDS
-      const auto sw = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(uint32_t, mx), __builtin_bit_cast(uint32_t, mx), false, false);
-      mx = fmaxf(__builtin_bit_cast(float, sw[0]), __builtin_bit_cast(float, sw[1]));
-    }
+    mx = max_with_other_half(mx);  // the other 32 keys of the row's stage
     // A stage that lies entirely past N (second half of a ragged last block) has mx = -inf.
     const float m_new = fmaxf(m_run, mx);
     if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {  // some row of this wave got a new maximum
@@ -303,6 +298,7 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_fwd_kernel(const FwdArgs a)
         }
       }
     key0 = key0_next;
+    k_at = k_at_next;
   }
 
   // ---- epilogue: O / l, LSE ----------------------------------------------------------------
@@ -332,7 +328,10 @@ int launch(const FwdArgs& a, hipStream_t stream) {
   const int64_t grid = 8LL * a.B * a.H * a.max_slice;
   if (grid > 0x7fffffffLL) return fail(RADIAL_ESHAPE, "B*H*n_blocks is too large for one launch");
   if (grid == 0) return RADIAL_OK;
-  radial_fwd_kernel<D, BLK><<<dim3((unsigned)grid), dim3(Tile<D, BLK>::kThreads), 0, stream>>>(a);
+  if (a.rule.exact)
+    radial_fwd_kernel<D, BLK, true><<<dim3((unsigned)grid), dim3(Tile<D, BLK>::kThreads), 0, stream>>>(a);
+  else
+    radial_fwd_kernel<D, BLK, false><<<dim3((unsigned)grid), dim3(Tile<D, BLK>::kThreads), 0, stream>>>(a);
   RADIAL_HIP_TRY(hipGetLastError());
   return RADIAL_OK;
 }

@@ -25,6 +25,8 @@ struct radial_mask {
   int32_t* d_slice_t = nullptr;  // [9]
   int32_t max_slice = 0;         // longest slice, in blocks (host copy, sizes the grid)
   int32_t max_slice_t = 0;
+  int32_t tokens_per_frame = 0;  // geometry of a radial mask (0 for dense / caller-supplied lists)
+  int32_t sink_frames = 0;
 };
 
 namespace radial {
@@ -38,6 +40,13 @@ int fail(int code, const char* fmt, ...);
     if (e_ != hipSuccess)                                                                 \
       return ::radial::fail(RADIAL_EHIP, "%s failed: %s", #expr, hipGetErrorString(e_));  \
   } while (0)
+
+// Token-level rule of the radial mask, for kernels that apply it inside listed blocks.
+struct TokenRule {
+  int32_t exact;  // 0: listed blocks are dense
+  int32_t s;      // tokens per frame
+  int32_t sink;   // key frames below this are visible to everyone
+};
 
 struct TensorArg {
   const void* ptr;
@@ -53,6 +62,7 @@ struct FwdArgs {
   int32_t max_slice;
   int32_t B, H, N, n_blocks;
   float scale;
+  TokenRule rule;
 };
 
 int launch_fwd(int D, int block, const FwdArgs& a, hipStream_t stream);
@@ -70,6 +80,7 @@ struct BwdArgs {
   int32_t max_slice, max_slice_t;
   int32_t B, H, N, n_blocks;
   float scale;
+  TokenRule rule;
 };
 
 int launch_bwd(int D, int block, const BwdArgs& a, hipStream_t stream);

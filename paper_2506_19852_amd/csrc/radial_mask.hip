@@ -230,7 +230,7 @@ __global__ void slice_kernel(const int32_t* ptr, int32_t nb, int32_t* slice) {
 
 int check_common(int64_t n_tokens, int32_t block, uint32_t flags) {
   if (block != 64 && block != 128) return fail(RADIAL_EUNSUPPORTED, "block must be 64 or 128 (got %d)", block);
-  if (flags & ~RADIAL_MASK_TRANSPOSE) return fail(RADIAL_EINVAL, "unknown mask flag bits 0x%x", flags);
+  if (flags & ~(RADIAL_MASK_TRANSPOSE | RADIAL_MASK_TOKEN_EXACT)) return fail(RADIAL_EINVAL, "unknown mask flag bits 0x%x", flags);
   if (n_tokens < 1 || n_tokens >= (int64_t)0x7fffffff - block)
     return fail(RADIAL_EINVAL, "token count %lld outside [1, 2^31 - block)", (long long)n_tokens);
   const int64_t nb = (n_tokens + block - 1) / block;
@@ -333,8 +333,12 @@ extern "C" int radial_mask_build(const radial_mask_params* p, void* hip_stream, 
   if (!p) return fail(RADIAL_EINVAL, "params is NULL");
   if (p->frames < 1 || p->tokens_per_frame < 1 || p->sink_frames < 0)
     return fail(RADIAL_EINVAL, "need frames >= 1, tokens_per_frame >= 1, sink_frames >= 0");
+  if ((p->flags & RADIAL_MASK_TOKEN_EXACT) && p->tokens_per_frame < 64)
+    return fail(RADIAL_EUNSUPPORTED, "RADIAL_MASK_TOKEN_EXACT needs tokens_per_frame >= 64");
   radial_mask* m = nullptr;
   if (int rc = new_mask((int64_t)p->frames * p->tokens_per_frame, p->block, p->flags, out, &m)) return rc;
+  m->tokens_per_frame = p->tokens_per_frame;
+  m->sink_frames = p->sink_frames;
   const int rc = build_radial(m, p, (hipStream_t)hip_stream);
   if (rc) {
     radial_mask_free(m);
@@ -357,6 +361,7 @@ static int build_dense(radial_mask* m, hipStream_t st) {
 
 extern "C" int radial_mask_build_dense(int32_t n_tokens, int32_t block, uint32_t flags, void* hip_stream,
                                        radial_mask** out) {
+  if (flags & RADIAL_MASK_TOKEN_EXACT) return fail(RADIAL_EINVAL, "RADIAL_MASK_TOKEN_EXACT applies to radial_mask_build only");
   radial_mask* m = nullptr;
   if (int rc = new_mask(n_tokens, block, flags, out, &m)) return rc;
   const int rc = build_dense(m, (hipStream_t)hip_stream);
@@ -391,6 +396,7 @@ static int build_from_csr(radial_mask* m, const int32_t* row_ptr, const int32_t*
 extern "C" int radial_mask_from_csr(int32_t n_tokens, int32_t block, uint32_t flags, const int32_t* row_ptr,
                                     const int32_t* col_idx, void* hip_stream, radial_mask** out) {
   if (!row_ptr) return fail(RADIAL_EINVAL, "row_ptr is NULL");
+  if (flags & RADIAL_MASK_TOKEN_EXACT) return fail(RADIAL_EINVAL, "RADIAL_MASK_TOKEN_EXACT applies to radial_mask_build only");
   radial_mask* m = nullptr;
   if (int rc = new_mask(n_tokens, block, flags, out, &m)) return rc;
   int rc = RADIAL_OK;

@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "radial_internal.h"
+
 namespace radial {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -94,6 +96,96 @@ struct SwzTile {
 __device__ __forceinline__ u32x2 lds_read_tr(const char* p) {
   const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(lds_cast<s16x4>(p));
   return __builtin_bit_cast(u32x2, v);
+}
+
+// max(x, value of x in lane^32), exchanged in registers (v_permlane32_swap: the upper 32 lanes
+// of the first operand trade places with the lower 32 lanes of the second).
+__device__ __forceinline__ float max_with_other_half(float x) {
+  const uint32_t u = __builtin_bit_cast(uint32_t, x);
+  const auto sw = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  // Copy the elements out before reinterpreting them: a bit_cast applied directly to
+  // sw[1] reads element 0.
+  const uint32_t first = sw[0], second = sw[1];
+  return fmaxf(__builtin_bit_cast(float, first), __builtin_bit_cast(float, second));
+}
+
+// ---- token-level rule of the radial mask inside listed blocks ---------------------------------
+// (Sec. 4.2 of the paper, formal definition, plus the attention sink of App. A.1.)
+
+// For one (query frame i, key frame j) pair: the largest |k - l| a query position k may
+// attend; -1 = nothing, >= s = the whole frame.
+__device__ __forceinline__ int32_t radial_half_width(int32_t s, int32_t sink, int32_t i, int32_t j) {
+  if (j < sink) return s;
+  const int32_t d = i > j ? i - j : j - i;
+  const int32_t r = 31 - __clz(d < 1 ? 1 : d);  // floor(log2 max(d, 1))
+  if ((1 << r) <= s) return (s >> r) - 1;       // diagonal of width floor(s / 2^r)
+  const int32_t stride = (int32_t)((((int64_t)1 << r) + s - 1) / s);
+  return d % stride == 0 ? 0 : -1;              // sub-sampled single diagonals
+}
+
+// A stage is 64 consecutive tokens (keys for the query-stationary kernels, queries for the
+// key-stationary one) that start at (frame, pos).  With s >= 64 it touches at most the two
+// frames `frame` and `frame + 1`.
+struct StagePos {
+  int32_t frame, pos;
+};
+
+// (frame, position) of token index `block_start` for every lane's list entry.
+__device__ __forceinline__ StagePos block_pos(int32_t block_start, int32_t s) {
+  StagePos r;
+  r.frame = block_start / s;
+  r.pos = block_start - r.frame * s;
+  return r;
+}
+
+// Entry `idx` of the per-lane positions, advanced by `offset` (< 128) tokens; wave-uniform.
+__device__ __forceinline__ StagePos stage_pos(StagePos per_lane, int idx, int32_t offset, int32_t s) {
+  StagePos r;
+  r.frame = __builtin_amdgcn_readlane(per_lane.frame, idx);
+  r.pos = __builtin_amdgcn_readlane(per_lane.pos, idx) + offset;
+  if (r.pos >= s) {
+    r.pos -= s;
+    r.frame += 1;
+  }
+  return r;
+}
+
+// What one lane's token (its own frame/position, a query or a key) sees of a stage: tokens
+// [lo0, lo0 + n0) of the stage's first frame and [lo1, lo1 + n1) of its second, as offsets
+// 0..63 into the stage.
+struct StageRule {
+  int32_t lo0, lo1;
+  uint32_t n0, n1;
+  bool partial;  // wave-uniform: some lane of the wave has a hidden pair in this stage
+  bool none;     // wave-uniform: no lane of the wave has a visible pair in this stage
+
+  // token `x` (0..63) of the stage
+  __device__ __forceinline__ bool visible(int x) const {
+    return ((uint32_t)(x - lo0) < n0) | ((uint32_t)(x - lo1) < n1);  // n1 = 0 without a second frame
+  }
+};
+
+// own_is_query: the lane holds a query and the stage holds keys; otherwise the reverse.
+__device__ __forceinline__ StageRule stage_rule(const TokenRule& rule, StagePos own, StagePos stage, bool own_is_query) {
+  const int32_t s = rule.s;
+  const int32_t hw0 = own_is_query ? radial_half_width(s, rule.sink, own.frame, stage.frame)
+                                   : radial_half_width(s, rule.sink, stage.frame, own.frame);
+  const int32_t hw1 = own_is_query ? radial_half_width(s, rule.sink, own.frame, stage.frame + 1)
+                                   : radial_half_width(s, rule.sink, stage.frame + 1, own.frame);
+  const int32_t split = s - stage.pos;  // stage offset at which the second frame starts
+  StageRule r;
+  // first frame: positions stage.pos + x, x in [0, min(split, 64)), within hw0 of own.pos
+  const int32_t a0 = max(own.pos - hw0 - stage.pos, 0), b0 = min(own.pos + hw0 - stage.pos, min(split, 64) - 1);
+  r.lo0 = a0;
+  r.n0 = b0 >= a0 ? (uint32_t)(b0 - a0 + 1) : 0u;
+  // second frame: positions x - split, x in [split, 64), within hw1 of own.pos
+  const int32_t a1 = max(own.pos - hw1 + split, split), b1 = min(own.pos + hw1 + split, 63);
+  r.lo1 = a1;
+  r.n1 = b1 >= a1 ? (uint32_t)(b1 - a1 + 1) : 0u;
+  const bool all_visible = r.n0 + r.n1 == 64u;
+  r.partial = __builtin_amdgcn_ballot_w64(!all_visible) != 0;
+  r.none = __builtin_amdgcn_ballot_w64(r.n0 + r.n1 != 0u) == 0;
+  return r;
 }
 
 }  // namespace radial

@@ -121,6 +121,27 @@ def test_strided_layout_and_user_list():
     mask.free()
 
 
+def test_row_maximum_spans_all_keys_of_a_stage():
+    # Keys whose index has bit 2 set score +L, the others -L: the running maximum has to come
+    # from every key of a 64-key stage, or exp() of the difference overflows.
+    N, D, block = 512, 128, 128
+    print("fwd row maximum", flush=True)
+    g = torch.Generator(device="cpu").manual_seed(77)
+    u = torch.randn(D, generator=g)
+    u = u / u.norm()
+    q = (u[None, :] * 16.0 + 0.05 * torch.randn((N, D), generator=g)).to(torch.bfloat16)
+    sign = torch.where((torch.arange(N) & 4) != 0, 1.0, -1.0)
+    k = (sign[:, None] * u[None, :] * 16.0 + 0.05 * torch.randn((N, D), generator=g)).to(torch.bfloat16)
+    v = torch.randn((N, D), generator=g).to(torch.bfloat16)
+    q, k, v = (t.view(1, 1, N, D).to(DEV) for t in (q, k, v))
+    scale = 0.5                                       # logits about +-128
+    mask = rb.radial_mask_build_dense(N, block)
+    out, lse = _run_fwd(q, k, v, mask, scale)
+    bitmap = np.ones((N // block, N // block), dtype=bool)
+    _check_blocks(out, lse, q, k, v, bitmap, range(N // block), block, scale, [(0, 0)], "rowmax")
+    mask.free()
+
+
 def test_argument_errors():
     q = _randn_bf16((1, 1, 256, 64), 1)
     mask = rb.radial_mask_build(2, 128, 64, 1)
