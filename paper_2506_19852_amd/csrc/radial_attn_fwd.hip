@@ -38,6 +38,9 @@ struct Tile {
   static constexpr int kSteps = D / 16;            // MFMA k-steps of the S product
   static constexpr int kKeyTiles = kStageKeys / 32;
   static constexpr int kDTiles = D / 32;           // 32-wide d tiles of O
+  // MFMAs of the first product per copy of the next stage (copies are spread over that product)
+  static constexpr int kCopyEvery = (kKeyTiles * kSteps) / (2 * kLoadsPerWave);
+  static_assert(kCopyEvery >= 1, "more copies than MFMAs in the first product");
 };
 
 // Swizzle key of a 256-byte LDS line (16 pieces of 16 bytes); pieces move inside their line only.
@@ -178,35 +181,13 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_fwd_kernel(const FwdArgs a)
     issue_stage(key0, 0);
   }
 
-  for (int32_t u = 0; u < n_stage; ++u) {
-    const int buf = u & 1;
-    // First key of stage u+1.
-    int32_t key0_next = 0;
-    const bool has_next = u + 1 < n_stage;
-    if (has_next) {
-      const int32_t e1 = (u + 1) / T::kSubs;
-      if ((u + 1) % T::kSubs == 0 && (e1 & 63) == 0) {  // entering the next chunk of the list
-        cvec = nvec;
-        nvec = e1 + 64 + lane < n_list ? cols[e1 + 64 + lane] : 0;
-        if (kExact) cvec_at = block_pos(cvec * BLK, a.rule.s);
-      }
-      key0_next = __builtin_amdgcn_readlane(cvec, e1 & 63) * BLK + ((u + 1) % T::kSubs) * kStageKeys;
-      if (kExact) k_at_next = stage_pos(cvec_at, e1 & 63, ((u + 1) % T::kSubs) * kStageKeys, a.rule.s);
-    }
-
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's copies of stage u have landed
-    __syncthreads();                                  // ... and everyone's; stage u-1 is fully consumed
-    if (has_next) issue_stage(key0_next, buf ^ 1);
-
-    StageRule vis = {};
-    if (kExact) {
-      vis = stage_rule(a.rule, q_at, k_at, true);
-      if (vis.none) {  // nothing in this stage for any row of this wave
-        key0 = key0_next;
-        k_at = k_at_next;
-        continue;
-      }
-    }
+  // One stage: scores of 64 keys, online softmax, O update.  spread_lanes (all or none): also issue this
+  // wave's copies of the next stage between the MFMAs of the first product.
+  auto stage_body = [&](int buf, int32_t key0, int32_t key0_next, const StageRule& vis, uint64_t spread_lanes) {
+    const uint32_t kdst_next = lds_base + (buf ^ 1) * 2 * T::kStageBytes + wave * T::kLoadsPerWave * 1024;
+    const uint32_t vdst_next = kdst_next + T::kStageBytes;
+    const __bf16* kbase_next = kp + (int64_t)key0_next * a.k.sn;  // wave-uniform
+    const __bf16* vbase_next = vp + (int64_t)key0_next * a.v.sn;
     const char* lds_k = lds + buf * 2 * T::kStageBytes;
     const char* lds_v = lds_k + T::kStageBytes;
 
@@ -220,6 +201,14 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_fwd_kernel(const FwdArgs a)
       for (int t = 0; t < T::kSteps; ++t) {
         const bf16x8 kf = *lds_cast<const bf16x8>(lds_k + piece_offset<D, false>(kt * 32 + lq, 2 * t + g));
         s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[t], s[kt], 0, 0, 0);
+        {  // one copy of stage u+1 every kCopyEvery MFMAs
+          const int m = kt * T::kSteps + t + 1;
+          const int j = m / T::kCopyEvery - 1;
+          if (m % T::kCopyEvery == 0 && j < T::kLoadsPerWave)
+            copy16_to_lds_sv_masked(kbase_next, koff[j], kdst_next + j * 1024, spread_lanes);
+          else if (m % T::kCopyEvery == 0 && j < 2 * T::kLoadsPerWave)
+            copy16_to_lds_sv_masked(vbase_next, voff[j - T::kLoadsPerWave], vdst_next + (j - T::kLoadsPerWave) * 1024, spread_lanes);
+        }
       }
     }
 
@@ -297,6 +286,42 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_fwd_kernel(const FwdArgs a)
           o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vraw), pf, o[dt], 0, 0, 0);
         }
       }
+  };
+
+  for (int32_t u = 0; u < n_stage; ++u) {
+    const int buf = u & 1;
+    // First key of stage u+1.
+    int32_t key0_next = 0;
+    const bool has_next = u + 1 < n_stage;
+    if (has_next) {
+      const int32_t e1 = (u + 1) / T::kSubs;
+      if ((u + 1) % T::kSubs == 0 && (e1 & 63) == 0) {  // entering the next chunk of the list
+        cvec = nvec;
+        nvec = e1 + 64 + lane < n_list ? cols[e1 + 64 + lane] : 0;
+        if (kExact) cvec_at = block_pos(cvec * BLK, a.rule.s);
+      }
+      key0_next = __builtin_amdgcn_readlane(cvec, e1 & 63) * BLK + ((u + 1) % T::kSubs) * kStageKeys;
+      if (kExact) k_at_next = stage_pos(cvec_at, e1 & 63, ((u + 1) % T::kSubs) * kStageKeys, a.rule.s);
+    }
+
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's copies of stage u have landed
+    __syncthreads();                                  // ... and everyone's; stage u-1 is fully consumed
+
+    StageRule vis = {};
+    bool skip = false;
+    if (kExact) {
+      vis = stage_rule(a.rule, q_at, k_at, true);
+      skip = vis.none;  // nothing in this stage for any row of this wave
+    }
+    // The copies of stage u+1 are spread over the first product of stage u (a burst of copies
+    // would hold the wave at the memory pipeline before it reaches its first MFMA); only a
+    // ragged next stage, or a stage this wave skips, issues them in one go.
+    const bool spread = has_next && !skip && key0_next + kStageKeys <= a.N;
+    if (has_next && !spread) issue_stage(key0_next, buf ^ 1);
+    if (!skip) {
+      const uint32_t on = __builtin_amdgcn_readfirstlane(spread ? ~0u : 0u);  // wave-uniform by construction
+      stage_body(buf, key0, spread ? key0_next : key0, vis, ((uint64_t)on << 32) | on);
+    }
     key0 = key0_next;
     k_at = k_at_next;
   }
