@@ -15,6 +15,12 @@ Readings taken where the paper leaves a choice (each is also listed in the desig
   blocks tile the flattened token index from 0; a (query block, key block) pair is listed
   iff ANY token pair inside it is visible; a listed block is computed densely, so the
   function the library evaluates is Eq. 2 under the block-expanded mask.
+* Sparsity knob (App. D / Sec. 5.1 say the mask's sparsity is "adjusted" to a compute budget
+  without defining how): a rational width scale c = width_num / width_den applied to frame
+  pairs at distance >= 2 only.  There the diagonal width floor(s / 2^r) becomes
+  floor(c * s / 2^r), i.e. (|k-l|+1) * 2^r * width_den <= s * width_num, and once that width
+  drops below 1 the diagonal is kept every ceil(2^r / (c * s)) frames.  c = 1 is the printed
+  definition; frame pairs at distance 0 and 1 and the sink are never scaled.
 """
 from __future__ import annotations
 
@@ -34,31 +40,34 @@ def band_index(i: int, j: int) -> int:
     return r if j > i else (-r if j < i else 0)
 
 
-def token_visible(f: int, s: int, sink_frames: int, i: int, j: int, k: int, l: int) -> bool:
+def token_visible(f: int, s: int, sink_frames: int, i: int, j: int, k: int, l: int,
+                  width_num: int = 1, width_den: int = 1) -> bool:
     """One entry of the 4-D mask of Sec. 4.2 (formal definition) OR the sink of App. A.1."""
     assert 0 <= i < f and 0 <= j < f and 0 <= k < s and 0 <= l < s
+    assert width_num >= 1 and width_den >= 1
     if j < sink_frames:                                  # attention sink
         return True
     d = abs(i - j)
     b = pow2_floor(d)
-    if b <= s and (abs(k - l) + 1) * b <= s:             # case 1: diagonal of width floor(s/b)
+    num, den = (width_num, width_den) if d >= 2 else (1, 1)   # the knob leaves d = 0, 1 alone
+    if b * den <= s * num and (abs(k - l) + 1) * b * den <= s * num:   # case 1: width floor(c*s/b)
         return True
-    stride = -(-b // s)                                  # ceil(b / s)
+    stride = -(-(b * den) // (s * num))                  # ceil(b / (c*s))
     if d % stride == 0 and k == l:                       # case 2: sub-sampled single diagonals
         return True
     return False
 
 
-def token_mask_4d(f: int, s: int, sink_frames: int = 1) -> np.ndarray:
+def token_mask_4d(f: int, s: int, sink_frames: int = 1, width_num: int = 1, width_den: int = 1) -> np.ndarray:
     """The whole mask M~[i, j, k, l] as a bool array (small f*s only)."""
     i = np.arange(f, dtype=np.int64)[:, None, None, None]
     j = np.arange(f, dtype=np.int64)[None, :, None, None]
     k = np.arange(s, dtype=np.int64)[None, None, :, None]
     l = np.arange(s, dtype=np.int64)[None, None, None, :]
-    return _visible_arrays(s, sink_frames, i, j, k, l)
+    return _visible_arrays(s, sink_frames, i, j, k, l, width_num, width_den)
 
 
-def _visible_arrays(s, sink_frames, i, j, k, l):
+def _visible_arrays(s, sink_frames, i, j, k, l, width_num=1, width_den=1):
     d = np.abs(i - j)
     dm = np.maximum(d, 1)
     # floor(log2(dm)) via exact integer search (no floating point anywhere in the mask)
@@ -68,8 +77,10 @@ def _visible_arrays(s, sink_frames, i, j, k, l):
         r = r + (t > 1)
         t = t >> 1
     b = np.int64(1) << r
-    case1 = (b <= s) & ((np.abs(k - l) + 1) * b <= s)
-    stride = (b + s - 1) // s
+    num = np.where(d >= 2, np.int64(width_num), np.int64(1))
+    den = np.where(d >= 2, np.int64(width_den), np.int64(1))
+    case1 = (b * den <= s * num) & ((np.abs(k - l) + 1) * b * den <= s * num)
+    stride = (b * den + s * num - 1) // (s * num)
     case2 = ((d % stride) == 0) & (k == l)
     sink = j < sink_frames
     return case1 | case2 | sink
@@ -82,7 +93,7 @@ def flatten_mask(m4: np.ndarray) -> np.ndarray:
     return np.ascontiguousarray(m4.transpose(0, 2, 1, 3)).reshape(f * s, f * s)
 
 
-def token_mask_rows(f: int, s: int, sink_frames: int, rows) -> np.ndarray:
+def token_mask_rows(f: int, s: int, sink_frames: int, rows, width_num: int = 1, width_den: int = 1) -> np.ndarray:
     """Rows ``rows`` of the flattened token mask M, bool [len(rows), n]."""
     rows = np.asarray(rows, dtype=np.int64)
     n = f * s
@@ -91,7 +102,7 @@ def token_mask_rows(f: int, s: int, sink_frames: int, rows) -> np.ndarray:
     k = (rows % s)[:, None]
     j = (cols // s)[None, :]
     l = (cols % s)[None, :]
-    return _visible_arrays(s, sink_frames, i, j, k, l)
+    return _visible_arrays(s, sink_frames, i, j, k, l, width_num, width_den)
 
 
 def block_any(mask_rows: np.ndarray, block: int) -> np.ndarray:
@@ -103,7 +114,8 @@ def block_any(mask_rows: np.ndarray, block: int) -> np.ndarray:
     return m.reshape(r, nkb, block).any(axis=2)
 
 
-def block_mask(f: int, s: int, block: int, sink_frames: int = 1, qblocks=None) -> np.ndarray:
+def block_mask(f: int, s: int, block: int, sink_frames: int = 1, qblocks=None,
+               width_num: int = 1, width_den: int = 1) -> np.ndarray:
     """Block bitmap [len(qblocks), nkb]: entry true iff any token pair of the block pair is visible."""
     n = f * s
     nqb = -(-n // block)
@@ -112,7 +124,7 @@ def block_mask(f: int, s: int, block: int, sink_frames: int = 1, qblocks=None) -
     out = []
     for qb in qblocks:
         rows = np.arange(qb * block, min(n, (qb + 1) * block))
-        out.append(block_any(token_mask_rows(f, s, sink_frames, rows), block).any(axis=0))
+        out.append(block_any(token_mask_rows(f, s, sink_frames, rows, width_num, width_den), block).any(axis=0))
     return np.array(out, dtype=bool).reshape(len(out), -(-n // block))
 
 

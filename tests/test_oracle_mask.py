@@ -1,5 +1,6 @@
 """Pins of the mask oracle against what the paper and arithmetic fix (CPU only)."""
 import itertools
+from fractions import Fraction
 import math
 import os
 
@@ -252,3 +253,86 @@ def test_partial_scan_matches_full_scan():
 def test_expand_block_row():
     row = np.array([True, False, True])
     assert om.expand_block_row(row, 4, 10).tolist() == [True] * 4 + [False] * 4 + [True] * 2
+
+
+# ---- sparsity knob (width scale c = num/den on frame pairs at distance >= 2) --------------------
+# The paper only says the sparsity is adjusted; these pins fix the reading the oracle takes.
+
+SCALES = [(1, 1), (1, 2), (2, 3), (13, 20), (3, 2), (1, 7), (5, 1)]
+
+
+@pytest.mark.parametrize("f,s", [(7, 8), (12, 6), (17, 5), (9, 16), (40, 2)])
+def test_width_scale_of_one_is_the_printed_definition(f, s):
+    base = om.token_mask_4d(f, s, 1)
+    assert np.array_equal(om.token_mask_4d(f, s, 1, 1, 1), base)
+    assert np.array_equal(om.token_mask_4d(f, s, 1, 3, 3), base)          # only the ratio matters
+    assert np.array_equal(om.token_mask_4d(f, s, 1, 2, 4), om.token_mask_4d(f, s, 1, 1, 2))
+
+
+@pytest.mark.parametrize("num,den", SCALES)
+def test_width_scale_leaves_near_frames_and_sink_alone(num, den):
+    f, s = 12, 10
+    m = om.token_mask_4d(f, s, 1, num, den)
+    ref = om.token_mask_4d(f, s, 1)
+    for i in range(f):
+        for j in range(f):
+            if abs(i - j) <= 1 or j == 0:
+                assert np.array_equal(m[i, j], ref[i, j])
+                assert m[i, j].all()
+
+
+@pytest.mark.parametrize("num,den", SCALES)
+@pytest.mark.parametrize("f,s", [(20, 24), (33, 40), (12, 16), (9, 7)])
+def test_width_scale_diagonal_width_and_count(f, s, num, den):
+    # frame pair at distance d >= 2, band r = floor(log2 d): diagonal of width w = floor(c*s/2^r)
+    # (clipped to the frame), i.e. s*(2w-1) - w*(w-1) visible pairs; once w < 1, a single
+    # diagonal every ceil(2^r/(c*s)) frames.
+    m = om.token_mask_4d(f, s, 0, num, den)
+    for i in range(f):
+        for j in range(f):
+            d = abs(i - j)
+            if d < 2:
+                continue
+            r = int(math.floor(math.log2(d)))
+            w = (s * num) // (den * 2 ** r)
+            if w >= 1:
+                w = min(w, s)
+                assert int(m[i, j].sum()) == s * (2 * w - 1) - w * (w - 1), (i, j)
+                k = s // 2
+                row = np.flatnonzero(m[i, j, k])
+                assert row.min() == max(0, k - (w - 1)) and row.max() == min(s - 1, k + w - 1)
+            else:
+                stride = math.ceil(Fraction(2 ** r * den, s * num))
+                want = np.eye(s, dtype=bool) if d % stride == 0 else np.zeros((s, s), dtype=bool)
+                assert np.array_equal(m[i, j], want), (i, j)
+
+
+def test_width_scale_worked_example():
+    # f = 4, s = 2, c = 1/2, no sink, derived by hand: distances 0 and 1 are untouched (all four
+    # pairs); distance 2 has width floor(0.5*2/2) = 0 < 1 -> stride ceil(2/(0.5*2)) = 2, 2 % 2 = 0:
+    # the diagonal stays; distance 3 is in the same band (2^r = 2), 3 % 2 != 0: nothing.
+    m = om.flatten_mask(om.token_mask_4d(4, 2, 0, 1, 2)).astype(int)
+    full, diag, none = np.ones((2, 2), int), np.eye(2, dtype=int), np.zeros((2, 2), int)
+    want = np.block([[full, full, diag, none],
+                     [full, full, full, diag],
+                     [diag, full, full, full],
+                     [none, diag, full, full]])
+    assert np.array_equal(m, want)
+
+
+@pytest.mark.parametrize("num,den", SCALES)
+@pytest.mark.parametrize("f,s,block,sink", [(7, 8, 3, 1), (12, 6, 8, 0), (40, 2, 8, 1), (17, 5, 7, 1), (9, 16, 16, 0)])
+def test_width_scale_scalar_numpy_and_c_agree(f, s, block, sink, num, den):
+    n = f * s
+    brute = np.zeros((n, n), dtype=bool)
+    for i, j, k, l in itertools.product(range(f), range(f), range(s), range(s)):
+        brute[i * s + k, j * s + l] = om.token_visible(f, s, sink, i, j, k, l, num, den)
+    rows = om.token_mask_rows(f, s, sink, np.arange(n), num, den)
+    assert np.array_equal(rows, brute)
+    nb = -(-n // block)
+    want = np.zeros((nb, nb), dtype=bool)
+    for q, c in zip(*np.nonzero(brute)):
+        want[q // block, c // block] = True
+    got, total = obuild.mask_scan(f, s, block, sink, 0, None, num, den)
+    assert np.array_equal(got, want) and total == int(brute.sum())
+    assert np.array_equal(om.block_mask(f, s, block, sink, None, num, den), want)
