@@ -80,6 +80,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--token-exact", action="store_true",
                     help="apply the token-level rule inside the listed blocks (same blocks computed; default: block-dense)")
+    ap.add_argument("--width-scale", default="1/1", metavar="NUM/DEN",
+                    help="sparsity knob: scales the diagonal width of frame pairs at distance >= 2 (default 1/1 = the printed mask)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain device copy of q (known size) so a rocprofv3 --pmc run can scale FETCH_SIZE/WRITE_SIZE")
     args = ap.parse_args()
@@ -93,6 +95,7 @@ def main():
     from paper_2506_19852_amd import workloads as wl
 
     w = wl.WORKLOADS[args.workload]
+    width_num, width_den = (int(t) for t in args.width_scale.split("/"))
     dev = "cuda:0"
     torch.cuda.set_device(0)
     x = wl.make_inputs(w, dev)
@@ -106,7 +109,7 @@ def main():
         grads = [torch.empty_like(x["q"]) for _ in range(3)]
 
     def step(keep=None):
-        m = rb.radial_mask_build(w.frames, w.tokens_per_frame, w.block, 1, flags)
+        m = rb.radial_mask_build(w.frames, w.tokens_per_frame, w.block, 1, flags, width_num=width_num, width_den=width_den)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         rb.radial_attn_fwd(x["q"], x["k"], x["v"], out, lse, m, w.scale)
@@ -168,14 +171,16 @@ def main():
         "config": {"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "D": w.D, "frames": w.frames,
                    "tokens_per_frame": w.tokens_per_frame, "block": w.block, "sink_frames": 1,
                    "listed_block_pairs": int(row_ptr[-1]), "pass": "fwd+bwd" if w.backward else "fwd",
-                   "inside_listed_blocks": "token rule" if args.token_exact else "dense"},
+                   "inside_listed_blocks": "token rule" if args.token_exact else "dense",
+                   "width_scale": f"{width_num}/{width_den}",
+                   "block_sparsity": round(1.0 - float(row_ptr[-1]) / float((row_ptr.size - 1) ** 2), 4)},
         "fwd_kernel_ms": round(kernel_ms, 3),
         "dense_fwd_kernel_ms": round(dense_ms, 3),
         "dense_tflops": round(dense_flops / (dense_ms * 1e-3) / 1e12, 2),
         "speedup_vs_dense": round(dense_ms / kernel_ms, 3),
         "block_ratio_dense_over_radial": round(dense_flops / fwd_flops, 3),
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
+                     "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if (width_num == width_den and not args.token_exact) else None,
                      "kernel": "radial_fwd_kernel", "flops_per_launch": fwd_flops},
     }
     if not args.no_cpu_baseline:

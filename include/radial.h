@@ -54,6 +54,11 @@ RADIAL_API const char* radial_last_error(void);
  *      j < sink_frames                                   (attention sink, App. A.1), or
  *      b <= s and (|k-l| + 1) * b <= s                   (first case of the formal definition), or
  *      d mod ceil(b/s) == 0 and k == l                   (second case).
+ * Sparsity knob (the paper adjusts the mask's sparsity to a compute budget, Sec. 5.1 and
+ * App. D, without defining how; this is the reading taken here): for frame pairs with d >= 2
+ * the spatial extent is scaled by c = width_num / width_den, i.e. `s` in the two cases above
+ * is replaced by c*s:  b*width_den <= s*width_num and (|k-l|+1)*b*width_den <= s*width_num,
+ * or  d mod ceil(b*width_den / (s*width_num)) == 0 and k == l.  c = 1 is the printed mask.
  * Blocks of `block` consecutive flattened tokens tile [0, N) from 0 (the last one may be
  * ragged, and a block may straddle frames).  A (query block, key block) pair is listed iff
  * at least one of its token pairs may attend; a listed pair is computed densely. */
@@ -63,6 +68,8 @@ typedef struct {
   int32_t block;            /* 64 or 128                                                 */
   int32_t sink_frames;      /* >= 0; the paper uses 1; 0 disables the sink               */
   uint32_t flags;           /* RADIAL_MASK_* bits, others must be 0                      */
+  int32_t width_num;        /* sparsity knob c = width_num / width_den: both in [1, 32767] */
+  int32_t width_den;        /*   and tokens_per_frame * width_num < 2^31; 1, 1 = the paper */
 } radial_mask_params;
 
 #define RADIAL_MASK_TRANSPOSE 1u /* also build the per-key-block list of query blocks (needed by bwd) */

@@ -50,7 +50,7 @@ extern "C" int radial_attn_fwd(int32_t B, int32_t H, int32_t N, int32_t D, radia
   a.max_slice = mask->max_slice;
   a.B = B; a.H = H; a.N = N; a.n_blocks = mask->n_blocks;
   a.scale = scale;
-  a.rule = TokenRule{(mask->flags & RADIAL_MASK_TOKEN_EXACT) ? 1 : 0, mask->tokens_per_frame, mask->sink_frames};
+  a.rule = make_token_rule(mask);
   return launch_fwd(D, mask->block, a, (hipStream_t)hip_stream);
 }
 
@@ -90,6 +90,6 @@ extern "C" int radial_attn_bwd(int32_t B, int32_t H, int32_t N, int32_t D, radia
   a.slice_t = mask->d_slice_t; a.max_slice_t = mask->max_slice_t;
   a.B = B; a.H = H; a.N = N; a.n_blocks = mask->n_blocks;
   a.scale = scale;
-  a.rule = TokenRule{(mask->flags & RADIAL_MASK_TOKEN_EXACT) ? 1 : 0, mask->tokens_per_frame, mask->sink_frames};
+  a.rule = make_token_rule(mask);
   return launch_bwd(D, mask->block, a, (hipStream_t)hip_stream);
 }

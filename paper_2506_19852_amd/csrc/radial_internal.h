@@ -27,6 +27,7 @@ struct radial_mask {
   int32_t max_slice_t = 0;
   int32_t tokens_per_frame = 0;  // geometry of a radial mask (0 for dense / caller-supplied lists)
   int32_t sink_frames = 0;
+  int32_t width_num = 1, width_den = 1;  // sparsity knob of a radial mask
 };
 
 namespace radial {
@@ -46,7 +47,23 @@ struct TokenRule {
   int32_t exact;  // 0: listed blocks are dense
   int32_t s;      // tokens per frame
   int32_t sink;   // key frames below this are visible to everyone
+  // sparsity knob c = num/den for frame distances >= 2: the diagonal of band r is
+  // floor(c*s / 2^r) = w0 >> r wide, with w0 = floor(s*num/den)
+  int32_t w0;
+  int32_t den;
+  int64_t s_num;  // s * num
 };
+
+inline TokenRule make_token_rule(const radial_mask* m) {
+  TokenRule r;
+  r.exact = (m->flags & RADIAL_MASK_TOKEN_EXACT) ? 1 : 0;
+  r.s = m->tokens_per_frame;
+  r.sink = m->sink_frames;
+  r.s_num = (int64_t)m->tokens_per_frame * m->width_num;
+  r.den = m->width_den;
+  r.w0 = (int32_t)(r.s_num / m->width_den);
+  return r;
+}
 
 struct TensorArg {
   const void* ptr;

@@ -37,6 +37,8 @@ constexpr int kMaxWords = 15 * 1024;  // 60 KiB of LDS bitmap: up to 491 520 key
 
 struct MaskGeom {
   int32_t f, s, block, sink, n, nb;
+  int32_t w0, den;  // sparsity knob c = num/den (frame distances >= 2): w0 = floor(s*num/den)
+  int64_t s_num;    // s * num
 };
 
 __device__ inline int32_t pow2_floor(int32_t d) {
@@ -66,14 +68,15 @@ __device__ void row_bitmap(const MaskGeom g, int32_t qb, uint32_t* words, int32_
     if (j < g.sink) {
       llo = 0;
       lhi = g.s - 1;
-    } else if (b <= g.s) {
-      const int64_t w = g.s / b;
+    } else if (d < 2 || g.w0 / b >= 1) {
+      // diagonal of width floor(s/b), or floor(c*s/b) for the scaled distances d >= 2
+      const int64_t w = d < 2 ? g.s : (g.w0 / b < g.s ? g.w0 / b : g.s);
       llo = klo - (w - 1);
       if (llo < 0) llo = 0;
       lhi = khi + (w - 1);
       if (lhi > g.s - 1) lhi = g.s - 1;
     } else {
-      const int32_t stride = (int32_t)(((int64_t)b + g.s - 1) / g.s);
+      const int32_t stride = (int32_t)(((int64_t)b * g.den + g.s_num - 1) / g.s_num);
       if (d % stride != 0) continue;
       llo = klo;
       lhi = khi;
@@ -309,7 +312,9 @@ static int new_mask(int64_t n_tokens, int32_t block, uint32_t flags, radial_mask
 static int build_radial(radial_mask* m, const radial_mask_params* p, hipStream_t st) {
   const int32_t nb = m->n_blocks;
   const int32_t nwords = (nb + 31) / 32;
-  const MaskGeom g{p->frames, p->tokens_per_frame, p->block, p->sink_frames, m->n_tokens, nb};
+  const int64_t s_num = (int64_t)p->tokens_per_frame * p->width_num;
+  const MaskGeom g{p->frames, p->tokens_per_frame, p->block, p->sink_frames, m->n_tokens, nb,
+                   (int32_t)(s_num / p->width_den), p->width_den, s_num};
   long long* d_total = nullptr;
   long long total = 0;
   RADIAL_HIP_TRY(hipMalloc(&m->d_row_ptr, sizeof(int32_t) * (nb + 1)));
@@ -335,10 +340,16 @@ extern "C" int radial_mask_build(const radial_mask_params* p, void* hip_stream, 
     return fail(RADIAL_EINVAL, "need frames >= 1, tokens_per_frame >= 1, sink_frames >= 0");
   if ((p->flags & RADIAL_MASK_TOKEN_EXACT) && p->tokens_per_frame < 64)
     return fail(RADIAL_EUNSUPPORTED, "RADIAL_MASK_TOKEN_EXACT needs tokens_per_frame >= 64");
+  if (p->width_num < 1 || p->width_num > 32767 || p->width_den < 1 || p->width_den > 32767)
+    return fail(RADIAL_EINVAL, "width_num and width_den must be in [1, 32767] (1, 1 for the paper's mask)");
+  if ((int64_t)p->tokens_per_frame * p->width_num > 0x7fffffffLL)
+    return fail(RADIAL_EINVAL, "tokens_per_frame * width_num must be below 2^31");
   radial_mask* m = nullptr;
   if (int rc = new_mask((int64_t)p->frames * p->tokens_per_frame, p->block, p->flags, out, &m)) return rc;
   m->tokens_per_frame = p->tokens_per_frame;
   m->sink_frames = p->sink_frames;
+  m->width_num = p->width_num;
+  m->width_den = p->width_den;
   const int rc = build_radial(m, p, (hipStream_t)hip_stream);
   if (rc) {
     radial_mask_free(m);

@@ -120,14 +120,17 @@ __device__ __forceinline__ float max_with_other_half(float x) {
 // (Sec. 4.2 of the paper, formal definition, plus the attention sink of App. A.1.)
 
 // For one (query frame i, key frame j) pair: the largest |k - l| a query position k may
-// attend; -1 = nothing, >= s = the whole frame.
-__device__ __forceinline__ int32_t radial_half_width(int32_t s, int32_t sink, int32_t i, int32_t j) {
-  if (j < sink) return s;
+// attend; -1 = nothing, >= s - 1 = the whole frame.
+__device__ __forceinline__ int32_t radial_half_width(const TokenRule& rule, int32_t i, int32_t j) {
+  if (j < rule.sink) return rule.s;
   const int32_t d = i > j ? i - j : j - i;
-  const int32_t r = 31 - __clz(d < 1 ? 1 : d);  // floor(log2 max(d, 1))
-  if ((1 << r) <= s) return (s >> r) - 1;       // diagonal of width floor(s / 2^r)
-  const int32_t stride = (int32_t)((((int64_t)1 << r) + s - 1) / s);
-  return d % stride == 0 ? 0 : -1;              // sub-sampled single diagonals
+  if (d < 2) return rule.s - 1;            // band 0: the whole frame, never scaled
+  const int32_t r = 31 - __clz(d);         // floor(log2 d)
+  const int32_t w = rule.w0 >> r;          // diagonal width floor(c*s / 2^r)
+  if (w >= 1) return (w < rule.s ? w : rule.s) - 1;
+  const int64_t b_den = (int64_t)rule.den << r;
+  const int32_t stride = (int32_t)((b_den + rule.s_num - 1) / rule.s_num);
+  return d % stride == 0 ? 0 : -1;         // sub-sampled single diagonals
 }
 
 // A stage is 64 consecutive tokens (keys for the query-stationary kernels, queries for the
@@ -175,10 +178,10 @@ struct StageRule {
 // own_is_query: the lane holds a query and the stage holds keys; otherwise the reverse.
 __device__ __forceinline__ StageRule stage_rule(const TokenRule& rule, StagePos own, StagePos stage, bool own_is_query) {
   const int32_t s = rule.s;
-  const int32_t hw0 = own_is_query ? radial_half_width(s, rule.sink, own.frame, stage.frame)
-                                   : radial_half_width(s, rule.sink, stage.frame, own.frame);
-  const int32_t hw1 = own_is_query ? radial_half_width(s, rule.sink, own.frame, stage.frame + 1)
-                                   : radial_half_width(s, rule.sink, stage.frame + 1, own.frame);
+  const int32_t hw0 = own_is_query ? radial_half_width(rule, own.frame, stage.frame)
+                                   : radial_half_width(rule, stage.frame, own.frame);
+  const int32_t hw1 = own_is_query ? radial_half_width(rule, own.frame, stage.frame + 1)
+                                   : radial_half_width(rule, stage.frame + 1, own.frame);
   const int32_t split = s - stage.pos;  // stage offset at which the second frame starts
   StageRule r;
   // first frame: positions stage.pos + x, x in [0, min(split, 64)), within hw0 of own.pos

@@ -29,12 +29,12 @@ def test_binding_prototypes_and_error_string():
     out = ctypes.c_void_p()
     rc = lib.radial_mask_build(None, None, ctypes.byref(out))
     assert rc == -1 and "NULL" in binding.radial_last_error()
-    p = binding.radial_mask_params(4, 16, 100, 1, 0)
+    p = binding.radial_mask_params(4, 16, 100, 1, 0, 1, 1)
     rc = lib.radial_mask_build(ctypes.byref(p), None, ctypes.byref(out))
     assert rc == -4 and "block" in binding.radial_last_error()
-    p = binding.radial_mask_params(0, 16, 64, 1, 0)
+    p = binding.radial_mask_params(0, 16, 64, 1, 0, 1, 1)
     assert lib.radial_mask_build(ctypes.byref(p), None, ctypes.byref(out)) == -1
-    p = binding.radial_mask_params(4, 16, 64, 1, 8)
+    p = binding.radial_mask_params(4, 16, 64, 1, 8, 1, 1)
     assert lib.radial_mask_build(ctypes.byref(p), None, ctypes.byref(out)) == -1
     assert lib.radial_attn_bwd_workspace(1, 1, 64, 64, None) == 0
     lib.radial_mask_free(None)
