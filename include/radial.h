@@ -89,6 +89,22 @@ typedef struct radial_mask radial_mask;
  * unknown flag, N too large), EUNSUPPORTED (block), ENOMEM, EHIP. */
 RADIAL_API int radial_mask_build(const radial_mask_params* params, void* hip_stream, radial_mask** out);
 
+/* A banded static mask: query token (i,k) may attend key token (j,l) iff j < sink_frames or
+ * |k - l| <= half_width[|i - j|]  (an entry of -1 hides the whole frame pair).  This one rule
+ * covers the other static video masks the paper compares with (Sec. 3 and Sec. 5.1: the
+ * "spatial" and "temporal" head masks, sliding windows; App., comparison with other
+ * O(n log n) patterns: widths inversely proportional to the frame distance) and, while every
+ * width is at least one, the radial mask itself.  The paper defines none of them formally;
+ * the caller chooses the widths.
+ *   half_width : host, int32 [frames], read during the call only;
+ *   flags      : RADIAL_MASK_TRANSPOSE, RADIAL_MASK_TOKEN_EXACT (needs tokens_per_frame >= 64);
+ *   block lists as for radial_mask_build ("any" cover, ascending, ragged last block).
+ * Errors: EINVAL (NULL, f<1, s<1, sink<0, unknown flag, N too large), EUNSUPPORTED (block,
+ * token rule with short frames), ENOMEM, EHIP. */
+RADIAL_API int radial_mask_build_banded(int32_t frames, int32_t tokens_per_frame, int32_t block, int32_t sink_frames,
+                                        const int32_t* half_width, uint32_t flags, void* hip_stream,
+                                        radial_mask** out);
+
 /* The all-ones list over ceil(n_tokens/block)^2 block pairs: dense attention, Eq. 1.
  * `flags` as in radial_mask_params. */
 RADIAL_API int radial_mask_build_dense(int32_t n_tokens, int32_t block, uint32_t flags, void* hip_stream,

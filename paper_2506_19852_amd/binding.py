@@ -18,7 +18,7 @@ STATUS = {0: "RADIAL_OK", -1: "RADIAL_EINVAL", -2: "RADIAL_ENOMEM", -3: "RADIAL_
           -4: "RADIAL_EUNSUPPORTED", -5: "RADIAL_ESHAPE"}
 
 EXPORTS = (
-    "radial_last_error", "radial_mask_build", "radial_mask_build_dense", "radial_mask_from_csr",
+    "radial_last_error", "radial_mask_build", "radial_mask_build_banded", "radial_mask_build_dense", "radial_mask_from_csr",
     "radial_mask_info", "radial_mask_copy_to_host", "radial_mask_copy_transpose_to_host",
     "radial_mask_free", "radial_attn_fwd", "radial_attn_bwd_workspace", "radial_attn_bwd",
 )
@@ -57,6 +57,8 @@ def load():
     lib.radial_last_error.restype = ctypes.c_char_p
     lib.radial_last_error.argtypes = []
     lib.radial_mask_build.argtypes = [POINTER(radial_mask_params), c_void_p, POINTER(c_void_p)]
+    lib.radial_mask_build_banded.argtypes = [c_int32, c_int32, c_int32, c_int32, POINTER(c_int32), c_uint32, c_void_p,
+                                             POINTER(c_void_p)]
     lib.radial_mask_build_dense.argtypes = [c_int32, c_int32, c_uint32, c_void_p, POINTER(c_void_p)]
     lib.radial_mask_from_csr.argtypes = [c_int32, c_int32, c_uint32, c_void_p, c_void_p, c_void_p, POINTER(c_void_p)]
     lib.radial_mask_info.argtypes = [c_void_p, POINTER(c_int32), POINTER(c_int32), POINTER(c_int32),
@@ -124,6 +126,17 @@ def radial_mask_build(frames: int, tokens_per_frame: int, block: int, sink_frame
     p = radial_mask_params(frames, tokens_per_frame, block, sink_frames, flags, width_num, width_den)
     out = c_void_p()
     _check(load().radial_mask_build(byref(p), _stream_ptr(stream), byref(out)))
+    return RadialMask(out)
+
+
+def radial_mask_build_banded(frames: int, tokens_per_frame: int, block: int, sink_frames: int, half_width,
+                             flags: int = 0, stream=None) -> RadialMask:
+    hw = np.ascontiguousarray(half_width, dtype=np.int32)
+    if hw.shape != (frames,):
+        raise ValueError("half_width needs one entry per frame distance 0 .. frames-1")
+    out = c_void_p()
+    _check(load().radial_mask_build_banded(frames, tokens_per_frame, block, sink_frames,
+                                           hw.ctypes.data_as(POINTER(c_int32)), flags, _stream_ptr(stream), byref(out)))
     return RadialMask(out)
 
 

@@ -28,6 +28,7 @@ struct radial_mask {
   int32_t tokens_per_frame = 0;  // geometry of a radial mask (0 for dense / caller-supplied lists)
   int32_t sink_frames = 0;
   int32_t width_num = 1, width_den = 1;  // sparsity knob of a radial mask
+  int32_t* d_half_width = nullptr;       // [frames + 1] banded patterns only: half width per frame distance
 };
 
 namespace radial {
@@ -52,6 +53,7 @@ struct TokenRule {
   int32_t w0;
   int32_t den;
   int64_t s_num;  // s * num
+  const int32_t* half_width;  // banded patterns: device table by frame distance (null: radial rule)
 };
 
 inline TokenRule make_token_rule(const radial_mask* m) {
@@ -62,6 +64,7 @@ inline TokenRule make_token_rule(const radial_mask* m) {
   r.s_num = (int64_t)m->tokens_per_frame * m->width_num;
   r.den = m->width_den;
   r.w0 = (int32_t)(r.s_num / m->width_den);
+  r.half_width = m->d_half_width;
   return r;
 }
 

@@ -39,6 +39,9 @@ struct MaskGeom {
   int32_t f, s, block, sink, n, nb;
   int32_t w0, den;  // sparsity knob c = num/den (frame distances >= 2): w0 = floor(s*num/den)
   int64_t s_num;    // s * num
+  // banded patterns: device table [f + 1] of spatial half widths per frame distance (-1: none);
+  // null for the radial mask
+  const int32_t* half_width;
 };
 
 __device__ inline int32_t pow2_floor(int32_t d) {
@@ -68,6 +71,13 @@ __device__ void row_bitmap(const MaskGeom g, int32_t qb, uint32_t* words, int32_
     if (j < g.sink) {
       llo = 0;
       lhi = g.s - 1;
+    } else if (g.half_width) {
+      const int64_t hw = g.half_width[d];
+      if (hw < 0) continue;
+      llo = klo - hw;
+      if (llo < 0) llo = 0;
+      lhi = khi + hw;
+      if (lhi > g.s - 1) lhi = g.s - 1;
     } else if (d < 2 || g.w0 / b >= 1) {
       // diagonal of width floor(s/b), or floor(c*s/b) for the scaled distances d >= 2
       const int64_t w = d < 2 ? g.s : (g.w0 / b < g.s ? g.w0 / b : g.s);
@@ -288,6 +298,7 @@ extern "C" void radial_mask_free(radial_mask* m) {
   (void)hipFree(m->d_row_idx);
   (void)hipFree(m->d_slice);
   (void)hipFree(m->d_slice_t);
+  (void)hipFree(m->d_half_width);
   delete m;
 }
 
@@ -309,12 +320,13 @@ static int new_mask(int64_t n_tokens, int32_t block, uint32_t flags, radial_mask
   return RADIAL_OK;
 }
 
+// Lists of a radial mask (m->d_half_width null) or of a banded pattern (table already on the device).
 static int build_radial(radial_mask* m, const radial_mask_params* p, hipStream_t st) {
   const int32_t nb = m->n_blocks;
   const int32_t nwords = (nb + 31) / 32;
   const int64_t s_num = (int64_t)p->tokens_per_frame * p->width_num;
   const MaskGeom g{p->frames, p->tokens_per_frame, p->block, p->sink_frames, m->n_tokens, nb,
-                   (int32_t)(s_num / p->width_den), p->width_den, s_num};
+                   (int32_t)(s_num / p->width_den), p->width_den, s_num, m->d_half_width};
   long long* d_total = nullptr;
   long long total = 0;
   RADIAL_HIP_TRY(hipMalloc(&m->d_row_ptr, sizeof(int32_t) * (nb + 1)));
@@ -351,6 +363,40 @@ extern "C" int radial_mask_build(const radial_mask_params* p, void* hip_stream, 
   m->width_num = p->width_num;
   m->width_den = p->width_den;
   const int rc = build_radial(m, p, (hipStream_t)hip_stream);
+  if (rc) {
+    radial_mask_free(m);
+    return rc;
+  }
+  *out = m;
+  return RADIAL_OK;
+}
+
+extern "C" int radial_mask_build_banded(int32_t frames, int32_t tokens_per_frame, int32_t block, int32_t sink_frames,
+                                        const int32_t* half_width, uint32_t flags, void* hip_stream,
+                                        radial_mask** out) {
+  if (frames < 1 || tokens_per_frame < 1 || sink_frames < 0)
+    return fail(RADIAL_EINVAL, "need frames >= 1, tokens_per_frame >= 1, sink_frames >= 0");
+  if (!half_width) return fail(RADIAL_EINVAL, "half_width is NULL");
+  if ((flags & RADIAL_MASK_TOKEN_EXACT) && tokens_per_frame < 64)
+    return fail(RADIAL_EUNSUPPORTED, "RADIAL_MASK_TOKEN_EXACT needs tokens_per_frame >= 64");
+  radial_mask* m = nullptr;
+  if (int rc = new_mask((int64_t)frames * tokens_per_frame, block, flags, out, &m)) return rc;
+  m->tokens_per_frame = tokens_per_frame;
+  m->sink_frames = sink_frames;
+  // device table with one extra entry: the kernels also look up the distance to the frame after
+  // the last one (a stage of keys may run past the end of the sequence)
+  std::vector<int32_t> table((size_t)frames + 1, -1);
+  for (int32_t d = 0; d < frames; ++d) table[d] = half_width[d] < -1 ? -1 : half_width[d];
+  const hipStream_t st = (hipStream_t)hip_stream;
+  int rc = RADIAL_OK;
+  if (hipMalloc(&m->d_half_width, sizeof(int32_t) * table.size()) != hipSuccess ||
+      hipMemcpyAsync(m->d_half_width, table.data(), sizeof(int32_t) * table.size(), hipMemcpyHostToDevice, st) != hipSuccess ||
+      hipStreamSynchronize(st) != hipSuccess)
+    rc = fail(RADIAL_EHIP, "copying the half-width table failed");
+  if (!rc) {
+    const radial_mask_params p{frames, tokens_per_frame, block, sink_frames, flags, 1, 1};
+    rc = build_radial(m, &p, st);
+  }
   if (rc) {
     radial_mask_free(m);
     return rc;

@@ -124,6 +124,7 @@ __device__ __forceinline__ float max_with_other_half(float x) {
 __device__ __forceinline__ int32_t radial_half_width(const TokenRule& rule, int32_t i, int32_t j) {
   if (j < rule.sink) return rule.s;
   const int32_t d = i > j ? i - j : j - i;
+  if (rule.half_width) return rule.half_width[d];  // banded pattern: table lookup (d <= frames)
   if (d < 2) return rule.s - 1;            // band 0: the whole frame, never scaled
   const int32_t r = 31 - __clz(d);         // floor(log2 d)
   const int32_t w = rule.w0 >> r;          // diagonal width floor(c*s / 2^r)
