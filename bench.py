@@ -70,6 +70,67 @@ def cpu_baseline(w, x, row_ptr, col_idx, budget_s=12.0):
             "sample": f"{done} of {nb} query blocks of head 0 ({w.name}), float64 numpy, {dt:.1f} s"}
 
 
+def complexity_curve(frames_list, heads, args):
+    """Forward time under the radial list and under the all-ones list as the video grows (frames
+    of the 720p geometry, s = 3600): the empirical form of the paper's O(n log n) claim (Fig. 2,
+    Sec. 4.2 complexity analysis).  Prints one JSON line per length, then a summary line."""
+    import dataclasses
+    import numpy as np
+    import torch
+    from paper_2506_19852_amd import binding as rb
+    from paper_2506_19852_amd import workloads as wl
+
+    base = wl.WORKLOADS["cfg3_hunyuan720p"]
+    width_num, width_den = (int(t) for t in args.width_scale.split("/"))
+    rows = []
+    for f in frames_list:
+        w = dataclasses.replace(base, name=f"hunyuan720p_f{f}", frames=f, H=heads)
+        x = {nm: wl.make_tensor(w, nm, "cuda:0") for nm in ("q", "k", "v")}
+        out = torch.empty_like(x["q"])
+        res = {}
+        for kind in ("radial", "dense"):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            if kind == "radial":
+                m = rb.radial_mask_build(w.frames, w.tokens_per_frame, w.block, 1, 0, width_num=width_num, width_den=width_den)
+            else:
+                m = rb.radial_mask_build_dense(w.N, w.block)
+            torch.cuda.synchronize()
+            build_ms = (time.perf_counter() - t0) * 1e3
+            ptr, idx = rb.radial_mask_copy_to_host(m)
+            flops = effective_flops(ptr, idx, w.N, w.block, w.D, w.B * w.H)
+            rb.radial_attn_fwd(x["q"], x["k"], x["v"], out, None, m, w.scale)      # warm-up
+            torch.cuda.synchronize()
+            steps = args.steps if kind == "radial" else max(1, args.dense_steps)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(steps):
+                rb.radial_attn_fwd(x["q"], x["k"], x["v"], out, None, m, w.scale)
+            e1.record()
+            torch.cuda.synchronize()
+            res[kind] = {"pairs": int(ptr[-1]), "ms": e0.elapsed_time(e1) / steps, "flops": flops, "mask_build_ms": build_ms}
+            m.free()
+        r, d = res["radial"], res["dense"]
+        row = {"frames": f, "N": w.N, "heads": heads, "listed_block_pairs": r["pairs"], "all_block_pairs": d["pairs"],
+               "radial_ms": round(r["ms"], 3), "dense_ms": round(d["ms"], 3),
+               "radial_tflops": round(r["flops"] / r["ms"] / 1e9, 1), "dense_tflops": round(d["flops"] / d["ms"] / 1e9, 1),
+               "speedup_vs_dense": round(d["ms"] / r["ms"], 3), "block_ratio_dense_over_radial": round(d["flops"] / r["flops"], 3),
+               "mask_build_ms": round(r["mask_build_ms"], 3)}
+        rows.append(row)
+        print(json.dumps(row), flush=True)
+        del x, out
+        torch.cuda.empty_cache()
+    # growth exponents between the first and the last length: time ~ N^p
+    a, b = rows[0], rows[-1]
+    ln = np.log(b["N"] / a["N"])
+    summary = {"curve": "forward time vs frames, s = 3600, block 128, D 128, width scale " + args.width_scale,
+               "exponent_radial_time": round(float(np.log(b["radial_ms"] / a["radial_ms"]) / ln), 3),
+               "exponent_dense_time": round(float(np.log(b["dense_ms"] / a["dense_ms"]) / ln), 3),
+               "exponent_listed_pairs": round(float(np.log(b["listed_block_pairs"] / a["listed_block_pairs"]) / ln), 3),
+               "pairs_per_n_log2f": [round(r["listed_block_pairs"] / (r["N"] / 128 * np.log2(r["frames"])), 2) for r in rows]}
+    print(json.dumps(summary))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -84,10 +145,17 @@ def main():
                     help="sparsity knob: scales the diagonal width of frame pairs at distance >= 2 (default 1/1 = the printed mask)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain device copy of q (known size) so a rocprofv3 --pmc run can scale FETCH_SIZE/WRITE_SIZE")
+    ap.add_argument("--curve-frames", default=None, metavar="F1,F2,...",
+                    help="instead of the benchmark line: forward time vs video length at the 720p geometry (s = 3600)")
+    ap.add_argument("--curve-heads", type=int, default=2)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
         sys.exit(2)
+
+    if args.curve_frames:
+        complexity_curve([int(t) for t in args.curve_frames.split(",")], args.curve_heads, args)
+        return
 
     import numpy as np
     import torch
