@@ -25,6 +25,8 @@ def _lib():
         _handle = ctypes.CDLL(build())
         _handle.radial_mask_scan.restype = ctypes.c_int64
         _handle.radial_mask_scan.argtypes = [ctypes.c_int32] * 8 + [ctypes.c_void_p]
+        _handle.radial_token_mask.restype = None
+        _handle.radial_token_mask.argtypes = [ctypes.c_int32] * 5 + [ctypes.c_int64] * 3 + [ctypes.c_void_p] * 2
     return _handle
 
 
@@ -38,3 +40,12 @@ def mask_scan(f: int, s: int, block: int, sink_frames: int, qb_begin: int = 0, q
     bitmap = np.zeros((qb_end - qb_begin, nb), dtype=np.uint8)
     total = _lib().radial_mask_scan(f, s, block, sink_frames, width_num, width_den, qb_begin, qb_end, bitmap.ctypes.data)
     return bitmap.astype(bool), int(total)
+
+
+def token_mask(f: int, s: int, sink_frames: int, q_begin: int, q_end: int, cols, width_num: int = 1, width_den: int = 1):
+    """Token mask entries M[q_begin:q_end, cols] by the C loop (same predicate as mask_scan): bool."""
+    cols = np.ascontiguousarray(cols, dtype=np.int64)
+    out = np.zeros((q_end - q_begin, cols.size), dtype=np.uint8)
+    _lib().radial_token_mask(f, s, sink_frames, width_num, width_den, q_begin, q_end, cols.size,
+                             cols.ctypes.data, out.ctypes.data)
+    return out.astype(bool)

@@ -105,6 +105,17 @@ def token_mask_rows(f: int, s: int, sink_frames: int, rows, width_num: int = 1, 
     return _visible_arrays(s, sink_frames, i, j, k, l, width_num, width_den)
 
 
+def token_mask_rows_cols(f: int, s: int, sink_frames: int, rows, cols, width_num: int = 1, width_den: int = 1) -> np.ndarray:
+    """Entries M[rows, cols] of the flattened token mask, bool [len(rows), len(cols)]."""
+    rows = np.asarray(rows, dtype=np.int64)
+    cols = np.asarray(cols, dtype=np.int64)
+    i = (rows // s)[:, None]
+    k = (rows % s)[:, None]
+    j = (cols // s)[None, :]
+    l = (cols % s)[None, :]
+    return _visible_arrays(s, sink_frames, i, j, k, l, width_num, width_den)
+
+
 def block_any(mask_rows: np.ndarray, block: int) -> np.ndarray:
     """OR-reduce the key axis of token-mask rows into key blocks: bool [rows, ceil(n/block)]."""
     r, n = mask_rows.shape

@@ -59,3 +59,17 @@ int64_t radial_mask_scan(int32_t f, int32_t s, int32_t block, int32_t sink_frame
     }
     return total;
 }
+
+/* Token mask entries M[q, cols[c]] for query rows [q_begin, q_end) and the given key columns:
+ * out is (q_end-q_begin) x ncols bytes, row-major, written 0/1.  Same visible() as the scan. */
+void radial_token_mask(int32_t f, int32_t s, int32_t sink_frames, int32_t width_num, int32_t width_den,
+                       int64_t q_begin, int64_t q_end, int64_t ncols, const int64_t *cols, uint8_t *out) {
+    (void)f;
+#pragma omp parallel for schedule(static)
+    for (int64_t q = q_begin; q < q_end; ++q) {
+        uint8_t *row = out + (size_t)(q - q_begin) * (size_t)ncols;
+        int64_t i = q / s, k = q % s;
+        for (int64_t c = 0; c < ncols; ++c)
+            row[c] = (uint8_t)visible(s, sink_frames, width_num, width_den, i, cols[c] / s, k, cols[c] % s);
+    }
+}

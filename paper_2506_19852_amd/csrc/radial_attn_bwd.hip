@@ -201,58 +201,111 @@ __global__ void __launch_bounds__(2 * BLK, 1) radial_bwd_dkdv_kernel(const BwdAr
       }
     }
 
+    // The stage is two 32-row halves (h = 0, 1).  One wave per SIMD has nobody to hide its LDS
+    // and VALU latencies behind, so the four products are software-pipelined by hand:
+    //   A: S, dP of half 0                    B: S, dP of half 1   | P, dS of half 0
+    //   C: dV, dK with half 0 | P, dS of half 1                    D: dV, dK with half 1
+    // LDS fragments are read kAhead MFMAs before their use and the scheduling fences keep the
+    // written order.
+    f32x16 s[2], dp[2];
+    uint32_t pp[2][8], dsp[2][8];
+    f32x4 lse4[2][4], dl4[2][4];
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
-      // S[q, key] and dP[q, key] for 32 query rows x this wave's 32 keys
-      f32x16 s, dp;
+    for (int h2 = 0; h2 < 2; ++h2) {
 #pragma unroll
-      for (int e = 0; e < 16; ++e) s[e] = dp[e] = 0.f;
+      for (int e = 0; e < 16; ++e) s[h2][e] = dp[h2][e] = 0.f;
 #pragma unroll
-      for (int t = 0; t < T::kSteps; ++t) {
-        const bf16x8 qfrag = *lds_cast<const bf16x8>(sq + QT::piece(qt * 32 + lq, 2 * t + g));
-        const bf16x8 gfrag = *lds_cast<const bf16x8>(sg + QT::piece(qt * 32 + lq, 2 * t + g));
-        s = mfma32(qfrag, kf[t], s);
-        dp = mfma32(gfrag, vf[t], dp);
+      for (int e4 = 0; e4 < 4; ++e4) {  // element 4*e4 + x: query row 32*h2 + 8*e4 + 4g + x of the stage
+        const int ql = h2 * 32 + 8 * e4 + 4 * g;
+        lse4[h2][e4] = *lds_cast<const f32x4>(st + ql * 4) * kLog2e;
+        dl4[h2][e4] = *lds_cast<const f32x4>(st + (kStageQ + ql) * 4);
       }
-      // element e: key = key_row (this lane), query = q0 + 32qt + 8(e/4) + 4g + e%4
-      if (kExact && vis.partial) {  // hidden pairs: P = exp(-inf) = 0
+    }
+    // P and dS of elements 2*pair, 2*pair + 1 of half h2 (key = this lane's, queries as above)
+    auto softmax_pair = [&](int h2, int pair) {
+      const int e = 2 * pair;
+      const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[h2][e], c, -lse4[h2][e >> 2][e & 3]));
+      const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[h2][e + 1], c, -lse4[h2][e >> 2][(e & 3) + 1]));
+      pp[h2][pair] = pack_bf16(p0, p1);
+      dsp[h2][pair] = pack_bf16(p0 * (dp[h2][e] - dl4[h2][e >> 2][e & 3]), p1 * (dp[h2][e + 1] - dl4[h2][e >> 2][(e & 3) + 1]));
+      // keeps this arithmetic where it is written (between two MFMAs) instead of next to its first use
+      asm volatile("" : "+v"(pp[h2][pair]), "+v"(dsp[h2][pair]));
+    };
+    // Rows that do not exist (ragged end) or that the token rule hides: P = exp(-inf) = 0, dS = 0.
+    auto hide = [&](int h2) {
+      if (ragged_q) {
 #pragma unroll
         for (int e = 0; e < 16; ++e)
-          if (!vis.visible(qt * 32 + 8 * (e >> 2) + 4 * g + (e & 3))) s[e] = -INFINITY;
+          if (q0 + h2 * 32 + 8 * (e >> 2) + 4 * g + (e & 3) >= a.N) s[h2][e] = -INFINITY;
       }
-      uint32_t pp[8], dsp[8];
+      if (kExact && vis.partial) {
 #pragma unroll
-      for (int e4 = 0; e4 < 4; ++e4) {
-        const int ql = qt * 32 + 8 * e4 + 4 * g;
-        const f32x4 lse4 = *lds_cast<const f32x4>(st + ql * 4);
-        const f32x4 dl4 = *lds_cast<const f32x4>(st + (kStageQ + ql) * 4);
-        float p[4], ds[4];
-#pragma unroll
-        for (int x = 0; x < 4; ++x) {
-          p[x] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[4 * e4 + x], c, -lse4[x] * kLog2e));
-          if (!key_ok || (ragged_q && q0 + ql + x >= a.N)) p[x] = 0.f;
-          ds[x] = p[x] * (dp[4 * e4 + x] - dl4[x]);
-        }
-        pp[2 * e4] = pack_bf16(p[0], p[1]);
-        pp[2 * e4 + 1] = pack_bf16(p[2], p[3]);
-        dsp[2 * e4] = pack_bf16(ds[0], ds[1]);
-        dsp[2 * e4 + 1] = pack_bf16(ds[2], ds[3]);
+        for (int e = 0; e < 16; ++e)
+          if (!vis.visible(h2 * 32 + 8 * (e >> 2) + 4 * g + (e & 3))) s[h2][e] = -INFINITY;
       }
-      // dV^T[d, key] += dO^T[d, q] P[q, key];  dK^T[d, key] += Q^T[d, q] dS[q, key]
+    };
+    constexpr int kAhead = 2;  // in units of one k-step (two fragments) or of one transposed fragment pair
+    bf16x8 qfr[2 * T::kSteps], gfr[2 * T::kSteps];
+    auto read_qg = [&](int i) {  // i = h2 * kSteps + t
+      const int h2 = i / T::kSteps, t = i % T::kSteps;
+      qfr[i] = *lds_cast<const bf16x8>(sq + QT::piece(h2 * 32 + lq, 2 * t + g));
+      gfr[i] = *lds_cast<const bf16x8>(sg + QT::piece(h2 * 32 + lq, 2 * t + g));
+    };
 #pragma unroll
-      for (int t2 = 0; t2 < 2; ++t2) {
-        const bf16x8 pf = as_bf16x8(pp[4 * t2], pp[4 * t2 + 1], pp[4 * t2 + 2], pp[4 * t2 + 3]);
-        const bf16x8 dsf = as_bf16x8(dsp[4 * t2], dsp[4 * t2 + 1], dsp[4 * t2 + 2], dsp[4 * t2 + 3]);
-        const int r0 = qt * 32 + 16 * t2 + 4 * g + (i16 >> 2);  // stage row of the first 4-row patch
+    for (int i = 0; i < kAhead; ++i) read_qg(i);
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- A: S, dP of half 0
 #pragma unroll
-        for (int dt = 0; dt < T::kDTiles; ++dt) {
-          const int col = 32 * dt + 16 * half16 + 4 * (i16 & 3);
-          const u32x2 g0 = lds_read_tr(sg + QT::elem(r0, col)), g1 = lds_read_tr(sg + QT::elem(r0 + 8, col));
-          dv[dt] = mfma32(as_bf16x8(g0[0], g0[1], g1[0], g1[1]), pf, dv[dt]);
-          const u32x2 q0v = lds_read_tr(sq + QT::elem(r0, col)), q1v = lds_read_tr(sq + QT::elem(r0 + 8, col));
-          dk[dt] = mfma32(as_bf16x8(q0v[0], q0v[1], q1v[0], q1v[1]), dsf, dk[dt]);
-        }
+    for (int t = 0; t < T::kSteps; ++t) {
+      read_qg(t + kAhead);  // runs into half 1
+      s[0] = mfma32(qfr[t], kf[t], s[0]);
+      dp[0] = mfma32(gfr[t], vf[t], dp[0]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    hide(0);
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- B: S, dP of half 1 | P, dS of half 0
+#pragma unroll
+    for (int t = 0; t < T::kSteps; ++t) {
+      if (t + kAhead < T::kSteps) read_qg(T::kSteps + t + kAhead);
+      s[1] = mfma32(qfr[T::kSteps + t], kf[t], s[1]);
+      dp[1] = mfma32(gfr[T::kSteps + t], vf[t], dp[1]);
+      if (t * 8 / T::kSteps != (t + 1) * 8 / T::kSteps) softmax_pair(0, t * 8 / T::kSteps);
+      if (T::kSteps == 4) softmax_pair(0, 2 * t + 1);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    hide(1);
+    // dV^T[d, key] += dO^T[d, q] P[q, key];  dK^T[d, key] += Q^T[d, q] dS[q, key]:
+    // fragment pair j = ((h2 * 2 + t2) * kDTiles + dt): transposed reads of dO and Q
+    constexpr int kPairs = 2 * 2 * T::kDTiles;
+    u32x4 gtr[kPairs], qtr[kPairs];
+    auto read_tr = [&](int j) {
+      const int h2 = j / (2 * T::kDTiles), t2 = (j / T::kDTiles) % 2, dt = j % T::kDTiles;
+      const int r0 = h2 * 32 + 16 * t2 + 4 * g + (i16 >> 2);  // stage row of the first 4-row patch
+      const int col = 32 * dt + 16 * half16 + 4 * (i16 & 3);
+      const u32x2 g0 = lds_read_tr(sg + QT::elem(r0, col)), g1 = lds_read_tr(sg + QT::elem(r0 + 8, col));
+      const u32x2 q0v = lds_read_tr(sq + QT::elem(r0, col)), q1v = lds_read_tr(sq + QT::elem(r0 + 8, col));
+      gtr[j] = u32x4{g0[0], g0[1], g1[0], g1[1]};
+      qtr[j] = u32x4{q0v[0], q0v[1], q1v[0], q1v[1]};
+    };
+#pragma unroll
+    for (int j = 0; j < kAhead; ++j) read_tr(j);
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- C: dV, dK with half 0 | P, dS of half 1;   D: dV, dK with half 1
+#pragma unroll
+    for (int j = 0; j < kPairs; ++j) {
+      if (j + kAhead < kPairs) read_tr(j + kAhead);
+      const int h2 = j / (2 * T::kDTiles), t2 = (j / T::kDTiles) % 2, dt = j % T::kDTiles;
+      const bf16x8 pf = as_bf16x8(pp[h2][4 * t2], pp[h2][4 * t2 + 1], pp[h2][4 * t2 + 2], pp[h2][4 * t2 + 3]);
+      const bf16x8 dsf = as_bf16x8(dsp[h2][4 * t2], dsp[h2][4 * t2 + 1], dsp[h2][4 * t2 + 2], dsp[h2][4 * t2 + 3]);
+      dv[dt] = mfma32(__builtin_bit_cast(bf16x8, gtr[j]), pf, dv[dt]);
+      dk[dt] = mfma32(__builtin_bit_cast(bf16x8, qtr[j]), dsf, dk[dt]);
+      if (h2 == 0) {  // the 8 softmax pairs of half 1 spread over the 2 * kDTiles steps of half 0
+        const int n0 = j * 8 / (2 * T::kDTiles), n1 = (j + 1) * 8 / (2 * T::kDTiles);
+#pragma unroll
+        for (int pair = n0; pair < n1; ++pair) softmax_pair(1, pair);
       }
+      __builtin_amdgcn_sched_barrier(0);
     }
     q0 = q0_next;
     q_at = q_at_next;

@@ -31,7 +31,7 @@ def _check_fwd_blocks(out, lse, q, k, v, f, s, sink, block, qblocks, scale, pair
         lh = lse[b, h].cpu().numpy()
         for qb in qblocks:
             rows = np.arange(qb * block, min(n, (qb + 1) * block))
-            vis = om.token_mask_rows(f, s, sink, rows)
+            vis = obuild.token_mask(f, s, sink, int(rows[0]), int(rows[-1]) + 1, np.arange(n))
             ref_o, ref_l, _ = oa.attention_rows(qh[rows], kh, vh, vis, scale)
             err, _ = assert_close(oh[rows], ref_o, f"{what} b{b} h{h} qb{qb} O")
             worst = max(worst, err)
@@ -152,7 +152,7 @@ def test_backward_small(f, s, block, D, B, H, sink, qscale):
     scale = 1.0 / np.sqrt(D)
     mask = rb.radial_mask_build(f, s, block, sink, rb.RADIAL_MASK_TRANSPOSE | EXACT)
     _, _, dq, dk, dv = _fwd_bwd(q, k, v, do, mask, scale)
-    vis = om.token_mask_rows(f, s, sink, np.arange(N))
+    vis = obuild.token_mask(f, s, sink, 0, N, np.arange(N))
     for b in range(B):
         for h in range(H):
             qh, kh, vh, gh = (t[b, h].float().cpu().numpy() for t in (q, k, v, do))
@@ -162,7 +162,7 @@ def test_backward_small(f, s, block, D, B, H, sink, qscale):
     mask.free()
 
 
-def test_workload_backward():
+def test_workload_backward(capsys):
     """Forward+backward workload at full size under the token rule: dQ of sampled query blocks
     and dK/dV of one key block, each against the oracle with the token mask."""
     w = wl.WORKLOADS["cfg5_wan480p_4x_bwd"]
@@ -178,27 +178,33 @@ def test_workload_backward():
     def block_grads(qb):
         """dQ of query block qb and its dK/dV contributions, on the keys it can see."""
         rows = np.arange(qb * block, min(w.N, (qb + 1) * block))
-        vis = om.token_mask_rows(f, s, 1, rows)
-        keys = np.flatnonzero(vis.any(axis=0))
-        g_q, g_k, g_v, _ = oa.attention_bwd_rows(qh[rows], kh[keys], vh[keys], vis[:, keys], w.scale, gh[rows])
+        listed, _ = obuild.mask_scan(f, s, block, 1, qb, qb + 1)          # candidate key blocks
+        cand = np.flatnonzero(om.expand_block_row(listed[0], block, w.N))
+        vis = obuild.token_mask(f, s, 1, int(rows[0]), int(rows[-1]) + 1, cand)
+        keep = vis.any(axis=0)
+        keys, vis = cand[keep], vis[:, keep]
+        g_q, g_k, g_v, _ = oa.attention_bwd_rows(qh[rows], kh[keys], vh[keys], vis, w.scale, gh[rows])
         return rows, keys, g_q, g_k, g_v
 
     rng = np.random.default_rng(w.seed + 2)
     for qb in sorted({0, nb - 1, s // block, *rng.integers(0, nb, 5).tolist()}):
         rows, _, ref_dq, _, _ = block_grads(qb)
         assert_close(dq[0, head, rows[0]:rows[-1] + 1].float().cpu().numpy(), ref_dq, f"exact cfg5 dQ qb{qb}")
-    kb = nb // 2 + 5
-    kcols = np.arange(kb * block, min(w.N, (kb + 1) * block))
     col_ptr, row_idx = rb.radial_mask_copy_transpose_to_host(mask)
+    kb = int(np.argmin(np.diff(col_ptr)[nb // 4: 3 * nb // 4])) + nb // 4    # the shortest column of the middle half
+    kcols = np.arange(kb * block, min(w.N, (kb + 1) * block))
     ref_dk = np.zeros((kcols.size, w.D))
     ref_dv = np.zeros((kcols.size, w.D))
     listers = row_idx[col_ptr[kb]:col_ptr[kb + 1]]
-    for qb in listers:
+    for n_done, qb in enumerate(listers):
         _, keys, _, g_k, g_v = block_grads(int(qb))
         pos = np.searchsorted(keys, kcols)
         hit = (pos < keys.size) & (keys[np.minimum(pos, keys.size - 1)] == kcols)
         ref_dk[hit] += g_k[pos[hit]]
         ref_dv[hit] += g_v[pos[hit]]
+        if n_done % 50 == 49:
+            with capsys.disabled():                                     # a sign of life for whoever watches the run
+                print(f" [cfg5 token-rule dK/dV: {n_done + 1}/{len(listers)} query blocks summed]", flush=True)
     assert_close(dk[0, head, kcols[0]:kcols[-1] + 1].float().cpu().numpy(), ref_dk, f"exact cfg5 dK kb{kb}")
     assert_close(dv[0, head, kcols[0]:kcols[-1] + 1].float().cpu().numpy(), ref_dv, f"exact cfg5 dV kb{kb}")
     print(f"cfg5 key block {kb}: {len(listers)} query blocks summed by the oracle", flush=True)

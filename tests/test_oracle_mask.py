@@ -336,3 +336,14 @@ def test_width_scale_scalar_numpy_and_c_agree(f, s, block, sink, num, den):
     got, total = obuild.mask_scan(f, s, block, sink, 0, None, num, den)
     assert np.array_equal(got, want) and total == int(brute.sum())
     assert np.array_equal(om.block_mask(f, s, block, sink, None, num, den), want)
+
+
+@pytest.mark.parametrize("num,den", [(1, 1), (13, 20), (1, 7)])
+@pytest.mark.parametrize("f,s,sink", [(7, 8, 1), (40, 2, 0), (17, 5, 2)])
+def test_c_token_mask_matches_numpy_rows(f, s, sink, num, den):
+    n = f * s
+    rng = np.random.default_rng(f * s)
+    cols = np.sort(rng.choice(n, size=max(1, n // 2), replace=False))
+    want = om.token_mask_rows(f, s, sink, np.arange(3, n - 2), num, den)[:, cols]
+    assert np.array_equal(obuild.token_mask(f, s, sink, 3, n - 2, cols, num, den), want)
+    assert np.array_equal(om.token_mask_rows_cols(f, s, sink, np.arange(3, n - 2), cols, num, den), want)
