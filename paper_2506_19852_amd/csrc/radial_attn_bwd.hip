@@ -134,7 +134,14 @@ __global__ void __launch_bounds__(2 * BLK, 1) radial_bwd_dkdv_kernel(const BwdAr
 #pragma unroll
   for (int i = 0; i < T::kQLoadsPerWave; ++i) QT::source_of((wave * T::kQLoadsPerWave + i) * 64 + lane, srow[i], scol[i]);
 
-  // Copies Q, dO (64 rows from q0) and their LSE / delta into stage buffer `buf`.
+  uint32_t qoff[T::kQLoadsPerWave], goff[T::kQLoadsPerWave];  // byte offsets from the stage's first row
+#pragma unroll
+  for (int i = 0; i < T::kQLoadsPerWave; ++i) {
+    qoff[i] = (uint32_t)(srow[i] * (int32_t)a.q.sn + scol[i]) * 2u;
+    goff[i] = (uint32_t)(srow[i] * (int32_t)a.dout.sn + scol[i]) * 2u;
+  }
+  // Copies Q, dO (64 rows from q0) and their LSE / delta into stage buffer `buf`, all at once
+  // (first stage, ragged stages; rows past N-1 are clamped to N-1).
   auto issue_stage = [&](int32_t q0, int buf) {
     const uint32_t qdst = lds_base + buf * T::kStageBytes + wave * T::kQLoadsPerWave * 1024;
     const uint32_t gdst = qdst + T::kQBytes;
@@ -185,21 +192,46 @@ __global__ void __launch_bounds__(2 * BLK, 1) radial_bwd_dkdv_kernel(const BwdAr
 
     wait_all_copies();  // stage u has landed
     __syncthreads();    // for every wave; stage u-1 is finished
-    if (has_next) issue_stage(q0_next, buf ^ 1);
+    // The copies of a full next stage are spread over the first MFMAs of this one (see below);
+    // a ragged one is issued at once.
+    const bool spread_next = has_next && q0_next + kStageQ <= a.N;
+    if (has_next && !spread_next) issue_stage(q0_next, buf ^ 1);
 
     const char* sq = lds + buf * T::kStageBytes;
     const char* sg = sq + T::kQBytes;
     const char* st = sg + T::kQBytes;  // 64 x LSE then 64 x delta
     const bool ragged_q = q0 + kStageQ > a.N;
     StageRule vis = {};
-    if (kExact) {
-      vis = stage_rule(a.rule, key_at, q_at, false);  // which of the stage's queries see this lane's key
-      if (vis.none) {  // no pair of this wave's keys with the stage's queries
-        q0 = q0_next;
-        q_at = q_at_next;
-        continue;
+    if (kExact) vis = stage_rule(a.rule, key_at, q_at, false);  // which of the stage's queries see this lane's key
+    uint32_t hidden = 0u;
+    if (ragged_q || (kExact && vis.partial)) {
+#pragma unroll
+      for (int i = 0; i < 32; ++i) {
+        const int row = (i >> 4) * 32 + 8 * ((i & 15) >> 2) + 4 * g + (i & 3);  // stage row of element i & 15 of half i >> 4
+        bool hide_it = q0 + row >= a.N;
+        if (kExact) hide_it = hide_it || !vis.visible(row);
+        hidden |= hide_it ? (1u << i) : 0u;
       }
     }
+    const bool any_hidden = __builtin_amdgcn_ballot_w64(hidden != 0u) != 0;
+    // this wave's copies of the next stage, one or two per k-step of phase A
+    const uint32_t on = __builtin_amdgcn_readfirstlane(spread_next ? ~0u : 0u);
+    const uint64_t copy_lanes = ((uint64_t)on << 32) | on;
+    const int32_t q_src = spread_next ? q0_next : q0;  // any valid row when the copies are switched off
+    const __bf16* qbase_next = qp + (int64_t)q_src * a.q.sn;
+    const __bf16* gbase_next = gp + (int64_t)q_src * a.dout.sn;
+    const uint32_t qdst_next = lds_base + (buf ^ 1) * T::kStageBytes + wave * T::kQLoadsPerWave * 1024;
+    const uint32_t gdst_next = qdst_next + T::kQBytes;
+    auto spread_copy = [&](int j) {  // j = 0 .. 2 * kQLoadsPerWave: Q pieces, dO pieces, LSE/delta
+      if (j < T::kQLoadsPerWave) {
+        copy16_to_lds_sv_masked(qbase_next, qoff[j], qdst_next + j * 1024, copy_lanes);
+      } else if (j < 2 * T::kQLoadsPerWave) {
+        copy16_to_lds_sv_masked(gbase_next, goff[j - T::kQLoadsPerWave], gdst_next + (j - T::kQLoadsPerWave) * 1024, copy_lanes);
+      } else if (j == 2 * T::kQLoadsPerWave) {
+        const uint32_t sdst = lds_base + (buf ^ 1) * T::kStageBytes + 2 * T::kQBytes + (wave & 1) * kStageQ * 4;
+        copy4_to_lds_sv_masked((wave == 0 ? lsep : deltap) + q_src, (uint32_t)lane * 4u, sdst, wave < 2 ? copy_lanes : 0ull);
+      }
+    };
 
     // The stage is two 32-row halves (h = 0, 1).  One wave per SIMD has nobody to hide its LDS
     // and VALU latencies behind, so the four products are software-pipelined by hand:
@@ -231,17 +263,13 @@ __global__ void __launch_bounds__(2 * BLK, 1) radial_bwd_dkdv_kernel(const BwdAr
       // keeps this arithmetic where it is written (between two MFMAs) instead of next to its first use
       asm volatile("" : "+v"(pp[h2][pair]), "+v"(dsp[h2][pair]));
     };
-    // Rows that do not exist (ragged end) or that the token rule hides: P = exp(-inf) = 0, dS = 0.
+    // Rows that do not exist (ragged end) or that the token rule hides get P = exp(-inf) = 0 and
+    // dS = 0.  Bit 16*h2 + e of `hidden` marks element e of half h2 for this lane.
     auto hide = [&](int h2) {
-      if (ragged_q) {
+      if (any_hidden) {
 #pragma unroll
         for (int e = 0; e < 16; ++e)
-          if (q0 + h2 * 32 + 8 * (e >> 2) + 4 * g + (e & 3) >= a.N) s[h2][e] = -INFINITY;
-      }
-      if (kExact && vis.partial) {
-#pragma unroll
-        for (int e = 0; e < 16; ++e)
-          if (!vis.visible(h2 * 32 + 8 * (e >> 2) + 4 * g + (e & 3))) s[h2][e] = -INFINITY;
+          if ((hidden >> (16 * h2 + e)) & 1u) s[h2][e] = -INFINITY;
       }
     };
     constexpr int kAhead = 2;  // in units of one k-step (two fragments) or of one transposed fragment pair
@@ -260,6 +288,9 @@ __global__ void __launch_bounds__(2 * BLK, 1) radial_bwd_dkdv_kernel(const BwdAr
       read_qg(t + kAhead);  // runs into half 1
       s[0] = mfma32(qfr[t], kf[t], s[0]);
       dp[0] = mfma32(gfr[t], vf[t], dp[0]);
+      constexpr int kCopies = 2 * T::kQLoadsPerWave + 1;
+#pragma unroll
+      for (int j = t * kCopies / T::kSteps; j < (t + 1) * kCopies / T::kSteps; ++j) spread_copy(j);
       __builtin_amdgcn_sched_barrier(0);
     }
     hide(0);

@@ -63,6 +63,12 @@ __device__ __forceinline__ void copy16_to_lds_sv_masked(const void* base, uint32
   asm volatile("s_mov_b32 m0, %1\n\ts_and_saveexec_b64 %0, %4\n\tglobal_load_lds_dwordx4 %2, %3\n\ts_mov_b64 exec, %0"
                : "=&s"(saved) : "s"(lds_addr), "v"(byte_offset), "s"(base), "s"(lanes) : "memory", "scc");
 }
+// The 4-byte form of copy16_to_lds_sv_masked (256 bytes per wave).
+__device__ __forceinline__ void copy4_to_lds_sv_masked(const void* base, uint32_t byte_offset, uint32_t lds_addr, uint64_t lanes) {
+  uint64_t saved;
+  asm volatile("s_mov_b32 m0, %1\n\ts_and_saveexec_b64 %0, %4\n\tglobal_load_lds_dword %2, %3\n\ts_mov_b64 exec, %0"
+               : "=&s"(saved) : "s"(lds_addr), "v"(byte_offset), "s"(base), "s"(lanes) : "memory", "scc");
+}
 // Same as copy16_to_lds with 4 bytes per lane (256 bytes per wave).
 __device__ __forceinline__ void copy4_to_lds(const void* gptr, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_addr), "v"(gptr) : "memory");
