@@ -496,20 +496,33 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_bwd_dq_kernel(const BwdArgs
     }
     wait_all_copies();
     __syncthreads();
-    if (has_next) issue_stage(key0_next, buf ^ 1);
 
     const char* lds_k = lds + buf * 2 * T::kTileBytes;
     const char* lds_v = lds_k + T::kTileBytes;
     const bool ragged = key0 + kStageKeys > a.N;
     StageRule vis = {};
+    bool skip = false;
     if (kExact) {
       vis = stage_rule(a.rule, q_at, k_at, true);  // which of the stage's keys this lane's query sees
-      if (vis.none) {  // no pair of this wave's queries with the stage's keys
-        key0 = key0_next;
-        k_at = k_at_next;
-        continue;
-      }
+      skip = vis.none;                             // no pair of this wave's queries with the stage's keys
     }
+    // The copies of a full next stage are spread over the MFMAs of the first key tile (a burst
+    // would hold the wave at the memory pipeline); a ragged next stage, or a stage this wave
+    // skips, issues them at once.
+    const bool spread = has_next && !skip && key0_next + kStageKeys <= a.N;
+    if (has_next && !spread) issue_stage(key0_next, buf ^ 1);
+    if (skip) {
+      key0 = key0_next;
+      k_at = k_at_next;
+      continue;
+    }
+    const uint32_t on = __builtin_amdgcn_readfirstlane(spread ? ~0u : 0u);
+    const uint64_t copy_lanes = ((uint64_t)on << 32) | on;
+    const int32_t key_src = spread ? key0_next : key0;  // any valid rows when the copies are switched off
+    const __bf16* kbase_next = kp + (int64_t)key_src * a.k.sn;
+    const __bf16* vbase_next = vp + (int64_t)key_src * a.v.sn;
+    const uint32_t kdst_next = lds_base + (buf ^ 1) * 2 * T::kTileBytes + wave * T::kLoadsPerWave * 1024;
+    const uint32_t vdst_next = kdst_next + T::kTileBytes;
 #pragma unroll
     for (int kt = 0; kt < kStageKeys / 32; ++kt) {
       // S^T[key, q] and dP^T[key, q] for 32 keys x this wave's 32 queries
@@ -522,6 +535,14 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_bwd_dq_kernel(const BwdArgs
         const bf16x8 vfrag = *lds_cast<const bf16x8>(lds_v + SW::piece(kt * 32 + lq, 2 * t + g));
         s = mfma32(kfrag, qf[t], s);
         dp = mfma32(vfrag, gf[t], dp);
+        if (kt == 0) {  // 2 * kLoadsPerWave copies over the kSteps steps of the first key tile
+          constexpr int kCopies = 2 * T::kLoadsPerWave;
+#pragma unroll
+          for (int j = t * kCopies / T::kSteps; j < (t + 1) * kCopies / T::kSteps; ++j) {
+            if (j < T::kLoadsPerWave) copy16_to_lds_sv_masked(kbase_next, koff[j], kdst_next + j * 1024, copy_lanes);
+            else copy16_to_lds_sv_masked(vbase_next, voff[j - T::kLoadsPerWave], vdst_next + (j - T::kLoadsPerWave) * 1024, copy_lanes);
+          }
+        }
       }
       // element e: key = key0 + 32kt + 8(e/4) + 4g + e%4, query = q_row (this lane)
       if (kExact && vis.partial) {  // hidden pairs: P = exp(-inf) = 0
