@@ -25,8 +25,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 # profiles/ (FETCH_SIZE scaled by 2.0, WRITE_SIZE by 1.0: what the same counters read for a
 # streaming kernel of known size in the same run).  None where no pass has been recorded.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg3_hunyuan720p": 2.35709e8 * 1024 * 2.0 + 7.24643e5 * 1024,
-    "cfg5_wan480p_4x_bwd": 3.82211e8 * 1024 * 2.0 + 1.2848e6 * 1024,
+    "cfg3_hunyuan720p": 2.35901e8 * 1024 * 2.0 + 7.2464e5 * 1024,
+    "cfg5_wan480p_4x_bwd": 3.84358e8 * 1024 * 2.0 + 1.28601e6 * 1024,
 }
 
 
