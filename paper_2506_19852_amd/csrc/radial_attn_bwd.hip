@@ -204,14 +204,10 @@ __global__ void __launch_bounds__(2 * BLK, 1) radial_bwd_dkdv_kernel(const BwdAr
     StageRule vis = {};
     if (kExact) vis = stage_rule(a.rule, key_at, q_at, false);  // which of the stage's queries see this lane's key
     uint32_t hidden = 0u;
-    if (ragged_q || (kExact && vis.partial)) {
-#pragma unroll
-      for (int i = 0; i < 32; ++i) {
-        const int row = (i >> 4) * 32 + 8 * ((i & 15) >> 2) + 4 * g + (i & 3);  // stage row of element i & 15 of half i >> 4
-        bool hide_it = q0 + row >= a.N;
-        if (kExact) hide_it = hide_it || !vis.visible(row);
-        hidden |= hide_it ? (1u << i) : 0u;
-      }
+    if (ragged_q || (kExact && vis.partial)) {  // query rows past N, rows the token rule hides from this key
+      uint64_t seen = stage_prefix(a.N - q0);
+      if (kExact) seen &= vis.visible_mask();
+      hidden = ~lane_element_bits(seen, g);
     }
     const bool any_hidden = __builtin_amdgcn_ballot_w64(hidden != 0u) != 0;
     // this wave's copies of the next stage, one or two per k-step of phase A
@@ -509,6 +505,13 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_bwd_dq_kernel(const BwdArgs
     // The copies of a full next stage are spread over the MFMAs of the first key tile (a burst
     // would hold the wave at the memory pipeline); a ragged next stage, or a stage this wave
     // skips, issues them at once.
+    uint32_t hidden = 0u;  // bit 16kt + e: element e of key tile kt is past N or hidden by the token rule
+    if (ragged || (kExact && vis.partial)) {
+      uint64_t seen = stage_prefix(a.N - key0);
+      if (kExact) seen &= vis.visible_mask();
+      hidden = ~lane_element_bits(seen, g);
+    }
+    const bool any_hidden = __builtin_amdgcn_ballot_w64(hidden != 0u) != 0;
     const bool spread = has_next && !skip && key0_next + kStageKeys <= a.N;
     if (has_next && !spread) issue_stage(key0_next, buf ^ 1);
     if (skip) {
@@ -545,21 +548,16 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_bwd_dq_kernel(const BwdArgs
         }
       }
       // element e: key = key0 + 32kt + 8(e/4) + 4g + e%4, query = q_row (this lane)
-      if (kExact && vis.partial) {  // hidden pairs: P = exp(-inf) = 0
+      if (any_hidden) {  // hidden pairs: P = exp(-inf) = 0
 #pragma unroll
         for (int e = 0; e < 16; ++e)
-          if (!vis.visible(kt * 32 + 8 * (e >> 2) + 4 * g + (e & 3))) s[e] = -INFINITY;
+          if ((hidden >> (16 * kt + e)) & 1u) s[e] = -INFINITY;
       }
       uint32_t dsp[8];
 #pragma unroll
       for (int e = 0; e < 16; e += 2) {
-        float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], c, -lse2));
-        float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e + 1], c, -lse2));
-        if (ragged) {
-          const int32_t key = key0 + kt * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
-          if (key >= a.N) p0 = 0.f;
-          if (key + 1 >= a.N) p1 = 0.f;
-        }
+        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], c, -lse2));
+        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e + 1], c, -lse2));
         dsp[e >> 1] = pack_bf16(p0 * (dp[e] - dlt), p1 * (dp[e + 1] - dlt));
       }
       // dQ^T[d, q] += K^T[d, key] dS^T[key, q]

@@ -213,23 +213,18 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_fwd_kernel(const FwdArgs a)
     }
 
     // ---- online softmax ------------------------------------------------------------------
-    // s[kt][e] belongs to key key0 + 32kt + 8(e/4) + 4g + e%4 and query q_row.
-    if (key0 + kStageKeys > a.N) {  // ragged end: keys >= N do not exist
-#pragma unroll
-      for (int kt = 0; kt < T::kKeyTiles; ++kt)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int32_t key = key0 + kt * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
-          if (key >= a.N) s[kt][e] = -INFINITY;
-        }
-    }
-    if (kExact) {  // keys the token rule hides from this lane's query
-      if (vis.partial) {
+    // s[kt][e] belongs to key key0 + 32kt + 8(e/4) + 4g + e%4 and query q_row.  Keys >= N do not
+    // exist; under the token rule some keys are hidden from this lane's query.
+    if (key0 + kStageKeys > a.N || (kExact && vis.partial)) {
+      uint64_t seen = stage_prefix(a.N - key0);
+      if (kExact) seen &= vis.visible_mask();
+      const uint32_t hidden = ~lane_element_bits(seen, g);
+      if (__builtin_amdgcn_ballot_w64(hidden != 0u) != 0) {
 #pragma unroll
         for (int kt = 0; kt < T::kKeyTiles; ++kt)
 #pragma unroll
           for (int e = 0; e < 16; ++e)
-            if (!vis.visible(kt * 32 + 8 * (e >> 2) + 4 * g + (e & 3))) s[kt][e] = -INFINITY;
+            if ((hidden >> (16 * kt + e)) & 1u) s[kt][e] = -INFINITY;
       }
     }
     float mx = s[0][0];

@@ -180,7 +180,32 @@ struct StageRule {
   __device__ __forceinline__ bool visible(int x) const {
     return ((uint32_t)(x - lo0) < n0) | ((uint32_t)(x - lo1) < n1);  // n1 = 0 without a second frame
   }
+  // bit x set iff token x of the stage is visible
+  __device__ __forceinline__ uint64_t visible_mask() const { return stage_interval(lo0, n0) | stage_interval(lo1, n1); }
+  // bits [lo, lo + n) of a 64-token stage (n = 0: none; lo + n <= 64 otherwise)
+  __device__ static __forceinline__ uint64_t stage_interval(int32_t lo, uint32_t n) {
+    if (n == 0u) return 0ull;
+    const uint64_t ones = n >= 64u ? ~0ull : ((1ull << n) - 1ull);
+    return ones << lo;
+  }
 };
+
+// The first `count` tokens of a stage (count >= 64: all of them): those that exist before N.
+__device__ __forceinline__ uint64_t stage_prefix(int32_t count) {
+  return count >= 64 ? ~0ull : (count <= 0 ? 0ull : ((1ull << count) - 1ull));
+}
+
+// An MFMA accumulator pair (two 32-token tiles of a stage) holds, in lane group g = lane/32,
+// element e of tile kt for stage token 32kt + 8(e/4) + 4g + e%4.  From a mask over the 64 stage
+// tokens this returns the lane's 32 bits in element order (bit 16kt + e): nibble g of every
+// byte of the mask, packed.
+__device__ __forceinline__ uint32_t lane_element_bits(uint64_t token_mask, int g) {
+  uint64_t v = (token_mask >> (4 * g)) & 0x0F0F0F0F0F0F0F0Full;
+  v = (v | (v >> 4)) & 0x00FF00FF00FF00FFull;
+  v = (v | (v >> 8)) & 0x0000FFFF0000FFFFull;
+  v = (v | (v >> 16));
+  return (uint32_t)v;
+}
 
 // own_is_query: the lane holds a query and the stage holds keys; otherwise the reverse.
 __device__ __forceinline__ StageRule stage_rule(const TokenRule& rule, StagePos own, StagePos stage, bool own_is_query) {
