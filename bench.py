@@ -143,6 +143,9 @@ def main():
                     help="apply the token-level rule inside the listed blocks (same blocks computed; default: block-dense)")
     ap.add_argument("--width-scale", default="1/1", metavar="NUM/DEN",
                     help="sparsity knob: scales the diagonal width of frame pairs at distance >= 2 (default 1/1 = the printed mask)")
+    ap.add_argument("--pattern", default="radial",
+                    help="mask: radial (default), or a banded comparison mask: spatial:W (frames), temporal:H (positions), "
+                         "sliding:W:H, harmonic")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain device copy of q (known size) so a rocprofv3 --pmc run can scale FETCH_SIZE/WRITE_SIZE")
     ap.add_argument("--curve-frames", default=None, metavar="F1,F2,...",
@@ -176,8 +179,18 @@ def main():
     if w.backward:
         grads = [torch.empty_like(x["q"]) for _ in range(3)]
 
+    def build_mask():
+        if args.pattern == "radial":
+            return rb.radial_mask_build(w.frames, w.tokens_per_frame, w.block, 1, flags, width_num=width_num, width_den=width_den)
+        from paper_2506_19852_amd import patterns
+        kind, *par = args.pattern.split(":")
+        par = [int(t) for t in par]
+        table = {"spatial": patterns.spatial_head, "temporal": patterns.temporal_head,
+                 "sliding": patterns.sliding_window, "harmonic": patterns.harmonic_decay}[kind](w.frames, w.tokens_per_frame, *par)
+        return rb.radial_mask_build_banded(w.frames, w.tokens_per_frame, w.block, 1, table, flags)
+
     def step(keep=None):
-        m = rb.radial_mask_build(w.frames, w.tokens_per_frame, w.block, 1, flags, width_num=width_num, width_den=width_den)
+        m = build_mask()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         rb.radial_attn_fwd(x["q"], x["k"], x["v"], out, lse, m, w.scale)
@@ -240,7 +253,7 @@ def main():
                    "tokens_per_frame": w.tokens_per_frame, "block": w.block, "sink_frames": 1,
                    "listed_block_pairs": int(row_ptr[-1]), "pass": "fwd+bwd" if w.backward else "fwd",
                    "inside_listed_blocks": "token rule" if args.token_exact else "dense",
-                   "width_scale": f"{width_num}/{width_den}",
+                   "width_scale": f"{width_num}/{width_den}", "pattern": args.pattern,
                    "block_sparsity": round(1.0 - float(row_ptr[-1]) / float((row_ptr.size - 1) ** 2), 4)},
         "fwd_kernel_ms": round(kernel_ms, 3),
         "dense_fwd_kernel_ms": round(dense_ms, 3),
@@ -248,7 +261,7 @@ def main():
         "speedup_vs_dense": round(dense_ms / kernel_ms, 3),
         "block_ratio_dense_over_radial": round(dense_flops / fwd_flops, 3),
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if (width_num == width_den and not args.token_exact) else None,
+                     "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if (width_num == width_den and not args.token_exact and args.pattern == "radial") else None,
                      "kernel": "radial_fwd_kernel", "flops_per_launch": fwd_flops},
     }
     if not args.no_cpu_baseline:
