@@ -24,21 +24,22 @@ def _lib():
     if _handle is None:
         _handle = ctypes.CDLL(build())
         _handle.radial_mask_scan.restype = ctypes.c_int64
-        _handle.radial_mask_scan.argtypes = [ctypes.c_int32] * 8 + [ctypes.c_void_p]
+        _handle.radial_mask_scan.argtypes = [ctypes.c_int32] * 9 + [ctypes.c_void_p]
         _handle.radial_token_mask.restype = None
         _handle.radial_token_mask.argtypes = [ctypes.c_int32] * 5 + [ctypes.c_int64] * 3 + [ctypes.c_void_p] * 2
     return _handle
 
 
 def mask_scan(f: int, s: int, block: int, sink_frames: int, qb_begin: int = 0, qb_end: int | None = None,
-              width_num: int = 1, width_den: int = 1):
+              width_num: int = 1, width_den: int = 1, extra_tokens: int = 0):
     """Brute-force block bitmap of query blocks [qb_begin, qb_end) and the visible-token-pair count."""
-    n = f * s
+    n = f * s + extra_tokens
     nb = -(-n // block)
     if qb_end is None:
         qb_end = nb
     bitmap = np.zeros((qb_end - qb_begin, nb), dtype=np.uint8)
-    total = _lib().radial_mask_scan(f, s, block, sink_frames, width_num, width_den, qb_begin, qb_end, bitmap.ctypes.data)
+    total = _lib().radial_mask_scan(f, s, block, sink_frames, width_num, width_den, extra_tokens, qb_begin, qb_end,
+                                    bitmap.ctypes.data)
     return bitmap.astype(bool), int(total)
 
 

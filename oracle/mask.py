@@ -21,6 +21,9 @@ Readings taken where the paper leaves a choice (each is also listed in the desig
   floor(c * s / 2^r), i.e. (|k-l|+1) * 2^r * width_den <= s * width_num, and once that width
   drops below 1 the diagonal is kept every ceil(2^r / (c * s)) frames.  c = 1 is the printed
   definition; frame pairs at distance 0 and 1 and the sink are never scaled.
+* Text tokens (the video models the paper evaluates append prompt tokens to the video
+  sequence, Sec. 5.1; the paper does not say how the mask treats them): ``extra_tokens``
+  tokens after the f*s video tokens attend to every token and are attended by every token.
 """
 from __future__ import annotations
 
@@ -164,3 +167,16 @@ def transpose_lists(row_ptr: np.ndarray, col_idx: np.ndarray, nkb: int):
 def expand_block_row(block_row: np.ndarray, block: int, n: int) -> np.ndarray:
     """Token-level visibility of one query block under block-dense semantics: bool [n]."""
     return np.repeat(block_row, block)[:n]
+
+
+def token_mask_rows_with_text(f: int, s: int, sink_frames: int, rows, extra_tokens: int,
+                              width_num: int = 1, width_den: int = 1) -> np.ndarray:
+    """Rows of the token mask of a sequence of f*s video tokens followed by extra_tokens text
+    tokens: bool [len(rows), f*s + extra_tokens]."""
+    rows = np.asarray(rows, dtype=np.int64)
+    nv = f * s
+    out = np.ones((rows.size, nv + extra_tokens), dtype=bool)          # text rows and text columns
+    video = rows < nv
+    if video.any():
+        out[np.flatnonzero(video), :nv] = token_mask_rows(f, s, sink_frames, rows[video], width_num, width_den)
+    return out

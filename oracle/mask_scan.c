@@ -35,9 +35,11 @@ static int visible(int64_t s, int64_t sink_frames, int64_t num, int64_t den,
 /* Scans query blocks [qb_begin, qb_end).  bitmap: (qb_end-qb_begin) x nkb bytes, row-major,
  * written 0/1.  Returns the number of visible token pairs among the scanned query rows. */
 int64_t radial_mask_scan(int32_t f, int32_t s, int32_t block, int32_t sink_frames,
-                         int32_t width_num, int32_t width_den,
+                         int32_t width_num, int32_t width_den, int32_t extra_tokens,
                          int32_t qb_begin, int32_t qb_end, uint8_t *bitmap) {
-    const int64_t n = (int64_t)f * s;
+    /* extra_tokens text tokens follow the f*s video tokens; they see and are seen by everyone */
+    const int64_t nv = (int64_t)f * s;
+    const int64_t n = nv + extra_tokens;
     const int64_t nkb = (n + block - 1) / block;
     int64_t total = 0;
     memset(bitmap, 0, (size_t)(qb_end - qb_begin) * (size_t)nkb);
@@ -50,7 +52,7 @@ int64_t radial_mask_scan(int32_t f, int32_t s, int32_t block, int32_t sink_frame
             int64_t i = q / s, k = q % s;
             for (int64_t c = 0; c < n; ++c) {
                 int64_t j = c / s, l = c % s;
-                if (visible(s, sink_frames, width_num, width_den, i, j, k, l)) {
+                if (q >= nv || c >= nv || visible(s, sink_frames, width_num, width_den, i, j, k, l)) {
                     row[c / block] = 1;
                     ++total;
                 }

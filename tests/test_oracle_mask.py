@@ -347,3 +347,21 @@ def test_c_token_mask_matches_numpy_rows(f, s, sink, num, den):
     want = om.token_mask_rows(f, s, sink, np.arange(3, n - 2), num, den)[:, cols]
     assert np.array_equal(obuild.token_mask(f, s, sink, 3, n - 2, cols, num, den), want)
     assert np.array_equal(om.token_mask_rows_cols(f, s, sink, np.arange(3, n - 2), cols, num, den), want)
+
+
+# ---- text tokens appended to the video sequence --------------------------------------------------
+
+@pytest.mark.parametrize("f,s,block,sink,extra", [(7, 8, 3, 1, 5), (12, 6, 8, 0, 1), (5, 12, 5, 1, 17), (9, 16, 16, 1, 16)])
+def test_text_tokens_see_and_are_seen_by_everyone(f, s, block, sink, extra):
+    nv, n = f * s, f * s + extra
+    full = om.token_mask_rows_with_text(f, s, sink, np.arange(n), extra)
+    assert full.shape == (n, n)
+    assert np.array_equal(full[:nv, :nv], om.token_mask_rows(f, s, sink, np.arange(nv)))   # video part unchanged
+    assert full[nv:].all() and full[:, nv:].all()
+    assert np.array_equal(om.token_mask_rows_with_text(f, s, sink, np.arange(nv), 0), full[:nv, :nv])
+    nb = -(-n // block)
+    want = np.zeros((nb, nb), dtype=bool)
+    for q, c in zip(*np.nonzero(full)):
+        want[q // block, c // block] = True
+    got, total = obuild.mask_scan(f, s, block, sink, 0, None, 1, 1, extra)
+    assert np.array_equal(got, want) and total == int(full.sum())
