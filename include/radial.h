@@ -59,6 +59,9 @@ RADIAL_API const char* radial_last_error(void);
  * the spatial extent is scaled by c = width_num / width_den, i.e. `s` in the two cases above
  * is replaced by c*s:  b*width_den <= s*width_num and (|k-l|+1)*b*width_den <= s*width_num,
  * or  d mod ceil(b*width_den / (s*width_num)) == 0 and k == l.  c = 1 is the printed mask.
+ * Text tokens (the video models of Sec. 5.1 append prompt tokens to the video sequence; the
+ * paper does not say how the mask treats them; reading taken here): `extra_tokens` tokens that
+ * follow the video tokens attend to every token and are attended by every token.
  * Blocks of `block` consecutive flattened tokens tile [0, N) from 0 (the last one may be
  * ragged, and a block may straddle frames).  A (query block, key block) pair is listed iff
  * at least one of its token pairs may attend; a listed pair is computed densely. */
@@ -70,6 +73,7 @@ typedef struct {
   uint32_t flags;           /* RADIAL_MASK_* bits, others must be 0                      */
   int32_t width_num;        /* sparsity knob c = width_num / width_den: both in [1, 32767] */
   int32_t width_den;        /*   and tokens_per_frame * width_num < 2^31; 1, 1 = the paper */
+  int32_t extra_tokens;     /* >= 0 text tokens after the f*s video tokens: N = f*s + extra */
 } radial_mask_params;
 
 #define RADIAL_MASK_TRANSPOSE 1u /* also build the per-key-block list of query blocks (needed by bwd) */

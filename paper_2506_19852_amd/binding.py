@@ -32,7 +32,8 @@ class RadialError(RuntimeError):
 
 class radial_mask_params(ctypes.Structure):
     _fields_ = [("frames", c_int32), ("tokens_per_frame", c_int32), ("block", c_int32),
-                ("sink_frames", c_int32), ("flags", c_uint32), ("width_num", c_int32), ("width_den", c_int32)]
+                ("sink_frames", c_int32), ("flags", c_uint32), ("width_num", c_int32), ("width_den", c_int32),
+                ("extra_tokens", c_int32)]
 
 
 class radial_tensor(ctypes.Structure):
@@ -122,8 +123,8 @@ class RadialMask:
 
 
 def radial_mask_build(frames: int, tokens_per_frame: int, block: int, sink_frames: int = 1, flags: int = 0,
-                      stream=None, width_num: int = 1, width_den: int = 1) -> RadialMask:
-    p = radial_mask_params(frames, tokens_per_frame, block, sink_frames, flags, width_num, width_den)
+                      stream=None, width_num: int = 1, width_den: int = 1, extra_tokens: int = 0) -> RadialMask:
+    p = radial_mask_params(frames, tokens_per_frame, block, sink_frames, flags, width_num, width_den, extra_tokens)
     out = c_void_p()
     _check(load().radial_mask_build(byref(p), _stream_ptr(stream), byref(out)))
     return RadialMask(out)

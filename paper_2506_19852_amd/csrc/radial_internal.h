@@ -28,6 +28,7 @@ struct radial_mask {
   int32_t tokens_per_frame = 0;  // geometry of a radial mask (0 for dense / caller-supplied lists)
   int32_t sink_frames = 0;
   int32_t width_num = 1, width_den = 1;  // sparsity knob of a radial mask
+  int32_t frames = 0;                    // video frames (tokens from frames*tokens_per_frame on are text tokens)
   int32_t* d_half_width = nullptr;       // [frames + 1] banded patterns only: half width per frame distance
 };
 
@@ -48,6 +49,7 @@ struct TokenRule {
   int32_t exact;  // 0: listed blocks are dense
   int32_t s;      // tokens per frame
   int32_t sink;   // key frames below this are visible to everyone
+  int32_t frames; // video frames; tokens of later "frames" are text tokens: they see and are seen by everyone
   // sparsity knob c = num/den for frame distances >= 2: the diagonal of band r is
   // floor(c*s / 2^r) = w0 >> r wide, with w0 = floor(s*num/den)
   int32_t w0;
@@ -61,6 +63,7 @@ inline TokenRule make_token_rule(const radial_mask* m) {
   r.exact = (m->flags & RADIAL_MASK_TOKEN_EXACT) ? 1 : 0;
   r.s = m->tokens_per_frame;
   r.sink = m->sink_frames;
+  r.frames = m->frames;
   r.s_num = (int64_t)m->tokens_per_frame * m->width_num;
   r.den = m->width_den;
   r.w0 = (int32_t)(r.s_num / m->width_den);

@@ -42,6 +42,7 @@ struct MaskGeom {
   // banded patterns: device table [f + 1] of spatial half widths per frame distance (-1: none);
   // null for the radial mask
   const int32_t* half_width;
+  int32_t nv;  // video tokens f*s; tokens nv .. n-1 are text tokens (dense rows and columns)
 };
 
 __device__ inline int32_t pow2_floor(int32_t d) {
@@ -56,6 +57,17 @@ __device__ void row_bitmap(const MaskGeom g, int32_t qb, uint32_t* words, int32_
   const int64_t q0 = (int64_t)qb * g.block;
   int64_t q1 = q0 + g.block - 1;
   if (q1 > (int64_t)g.n - 1) q1 = (int64_t)g.n - 1;
+  if (q1 >= g.nv) {  // the block holds a text token: it lists every key block
+    for (int32_t w = threadIdx.x; w < nwords; w += blockDim.x) {
+      const int32_t left = g.nb - w * 32;
+      words[w] = left >= 32 ? 0xffffffffu : ((1u << left) - 1u);
+    }
+    __syncthreads();
+    return;
+  }
+  if (g.nv < g.n) {  // every video row lists the text tokens' key blocks
+    for (int32_t kb = g.nv / g.block + threadIdx.x; kb < g.nb; kb += blockDim.x) atomicOr(&words[kb >> 5], 1u << (kb & 31));
+  }
   const int32_t i0 = (int32_t)(q0 / g.s), i1 = (int32_t)(q1 / g.s);
   const int64_t npairs = (int64_t)(i1 - i0 + 1) * g.f;
   for (int64_t p = threadIdx.x; p < npairs; p += blockDim.x) {
@@ -326,7 +338,8 @@ static int build_radial(radial_mask* m, const radial_mask_params* p, hipStream_t
   const int32_t nwords = (nb + 31) / 32;
   const int64_t s_num = (int64_t)p->tokens_per_frame * p->width_num;
   const MaskGeom g{p->frames, p->tokens_per_frame, p->block, p->sink_frames, m->n_tokens, nb,
-                   (int32_t)(s_num / p->width_den), p->width_den, s_num, m->d_half_width};
+                   (int32_t)(s_num / p->width_den), p->width_den, s_num, m->d_half_width,
+                   (int32_t)((int64_t)p->frames * p->tokens_per_frame)};
   long long* d_total = nullptr;
   long long total = 0;
   RADIAL_HIP_TRY(hipMalloc(&m->d_row_ptr, sizeof(int32_t) * (nb + 1)));
@@ -348,8 +361,8 @@ static int build_radial(radial_mask* m, const radial_mask_params* p, hipStream_t
 
 extern "C" int radial_mask_build(const radial_mask_params* p, void* hip_stream, radial_mask** out) {
   if (!p) return fail(RADIAL_EINVAL, "params is NULL");
-  if (p->frames < 1 || p->tokens_per_frame < 1 || p->sink_frames < 0)
-    return fail(RADIAL_EINVAL, "need frames >= 1, tokens_per_frame >= 1, sink_frames >= 0");
+  if (p->frames < 1 || p->tokens_per_frame < 1 || p->sink_frames < 0 || p->extra_tokens < 0)
+    return fail(RADIAL_EINVAL, "need frames >= 1, tokens_per_frame >= 1, sink_frames >= 0, extra_tokens >= 0");
   if ((p->flags & RADIAL_MASK_TOKEN_EXACT) && p->tokens_per_frame < 64)
     return fail(RADIAL_EUNSUPPORTED, "RADIAL_MASK_TOKEN_EXACT needs tokens_per_frame >= 64");
   if (p->width_num < 1 || p->width_num > 32767 || p->width_den < 1 || p->width_den > 32767)
@@ -357,8 +370,9 @@ extern "C" int radial_mask_build(const radial_mask_params* p, void* hip_stream, 
   if ((int64_t)p->tokens_per_frame * p->width_num > 0x7fffffffLL)
     return fail(RADIAL_EINVAL, "tokens_per_frame * width_num must be below 2^31");
   radial_mask* m = nullptr;
-  if (int rc = new_mask((int64_t)p->frames * p->tokens_per_frame, p->block, p->flags, out, &m)) return rc;
+  if (int rc = new_mask((int64_t)p->frames * p->tokens_per_frame + p->extra_tokens, p->block, p->flags, out, &m)) return rc;
   m->tokens_per_frame = p->tokens_per_frame;
+  m->frames = p->frames;
   m->sink_frames = p->sink_frames;
   m->width_num = p->width_num;
   m->width_den = p->width_den;
@@ -382,6 +396,7 @@ extern "C" int radial_mask_build_banded(int32_t frames, int32_t tokens_per_frame
   radial_mask* m = nullptr;
   if (int rc = new_mask((int64_t)frames * tokens_per_frame, block, flags, out, &m)) return rc;
   m->tokens_per_frame = tokens_per_frame;
+  m->frames = frames;
   m->sink_frames = sink_frames;
   // device table with one extra entry: the kernels also look up the distance to the frame after
   // the last one (a stage of keys may run past the end of the sequence)
@@ -394,7 +409,7 @@ extern "C" int radial_mask_build_banded(int32_t frames, int32_t tokens_per_frame
       hipStreamSynchronize(st) != hipSuccess)
     rc = fail(RADIAL_EHIP, "copying the half-width table failed");
   if (!rc) {
-    const radial_mask_params p{frames, tokens_per_frame, block, sink_frames, flags, 1, 1};
+    const radial_mask_params p{frames, tokens_per_frame, block, sink_frames, flags, 1, 1, 0};
     rc = build_radial(m, &p, st);
   }
   if (rc) {

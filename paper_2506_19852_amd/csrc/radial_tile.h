@@ -128,7 +128,7 @@ __device__ __forceinline__ float max_with_other_half(float x) {
 // For one (query frame i, key frame j) pair: the largest |k - l| a query position k may
 // attend; -1 = nothing, >= s - 1 = the whole frame.
 __device__ __forceinline__ int32_t radial_half_width(const TokenRule& rule, int32_t i, int32_t j) {
-  if (j < rule.sink) return rule.s;
+  if (j < rule.sink || i >= rule.frames || j >= rule.frames) return rule.s;  // sink, text tokens
   const int32_t d = i > j ? i - j : j - i;
   if (rule.half_width) return rule.half_width[d];  // banded pattern: table lookup (d <= frames)
   if (d < 2) return rule.s - 1;            // band 0: the whole frame, never scaled

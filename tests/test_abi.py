@@ -29,12 +29,12 @@ def test_binding_prototypes_and_error_string():
     out = ctypes.c_void_p()
     rc = lib.radial_mask_build(None, None, ctypes.byref(out))
     assert rc == -1 and "NULL" in binding.radial_last_error()
-    p = binding.radial_mask_params(4, 16, 100, 1, 0, 1, 1)
+    p = binding.radial_mask_params(4, 16, 100, 1, 0, 1, 1, 0)
     rc = lib.radial_mask_build(ctypes.byref(p), None, ctypes.byref(out))
     assert rc == -4 and "block" in binding.radial_last_error()
-    p = binding.radial_mask_params(0, 16, 64, 1, 0, 1, 1)
+    p = binding.radial_mask_params(0, 16, 64, 1, 0, 1, 1, 0)
     assert lib.radial_mask_build(ctypes.byref(p), None, ctypes.byref(out)) == -1
-    p = binding.radial_mask_params(4, 16, 64, 1, 8, 1, 1)
+    p = binding.radial_mask_params(4, 16, 64, 1, 8, 1, 1, 0)
     assert lib.radial_mask_build(ctypes.byref(p), None, ctypes.byref(out)) == -1
     assert lib.radial_attn_bwd_workspace(1, 1, 64, 64, None) == 0
     lib.radial_mask_free(None)
@@ -55,7 +55,7 @@ def test_header_is_plain_c_and_links(tmp_path):
 #include "radial.h"
 int main(void) {
   radial_mask* m = (radial_mask*)0;
-  radial_mask_params p = {4, 16, 100, 1, 0u, 1, 1};      /* unsupported block size */
+  radial_mask_params p = {4, 16, 100, 1, 0u, 1, 1, 0};      /* unsupported block size */
   if (radial_mask_build(&p, 0, &m) != RADIAL_EUNSUPPORTED || m) return 1;
   if (!strstr(radial_last_error(), "block")) return 2;
   p.block = 64; p.width_den = 0;                          /* bad sparsity knob */
