@@ -59,12 +59,16 @@ __device__ __forceinline__ void copy16_to_lds_sv(const void* base, uint32_t byte
 // copy16_to_lds_sv for the lanes set in `lanes` only (all or none in practice: with no lane the
 // instruction is a no-op, which lets straight-line code switch a copy off without a branch).
 __device__ __forceinline__ void copy16_to_lds_sv_masked(const void* base, uint32_t byte_offset, uint32_t lds_addr, uint64_t lanes) {
+  // `lanes` is wave-uniform by contract; say so to the compiler (the operand must be scalar)
+  lanes = ((uint64_t)__builtin_amdgcn_readfirstlane((uint32_t)(lanes >> 32)) << 32) | __builtin_amdgcn_readfirstlane((uint32_t)lanes);
   uint64_t saved;
   asm volatile("s_mov_b32 m0, %1\n\ts_and_saveexec_b64 %0, %4\n\tglobal_load_lds_dwordx4 %2, %3\n\ts_mov_b64 exec, %0"
                : "=&s"(saved) : "s"(lds_addr), "v"(byte_offset), "s"(base), "s"(lanes) : "memory", "scc");
 }
 // The 4-byte form of copy16_to_lds_sv_masked (256 bytes per wave).
 __device__ __forceinline__ void copy4_to_lds_sv_masked(const void* base, uint32_t byte_offset, uint32_t lds_addr, uint64_t lanes) {
+  // `lanes` is wave-uniform by contract; say so to the compiler (the operand must be scalar)
+  lanes = ((uint64_t)__builtin_amdgcn_readfirstlane((uint32_t)(lanes >> 32)) << 32) | __builtin_amdgcn_readfirstlane((uint32_t)lanes);
   uint64_t saved;
   asm volatile("s_mov_b32 m0, %1\n\ts_and_saveexec_b64 %0, %4\n\tglobal_load_lds_dword %2, %3\n\ts_mov_b64 exec, %0"
                : "=&s"(saved) : "s"(lds_addr), "v"(byte_offset), "s"(base), "s"(lanes) : "memory", "scc");
