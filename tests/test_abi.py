@@ -73,3 +73,22 @@ int main(void) {
                            str(src), "-o", str(exe), "-L", libdir, "-lradial", f"-Wl,-rpath,{libdir}"])
     out = subprocess.run([str(exe)], capture_output=True, text=True)
     assert out.returncode == 0 and out.stdout.strip() == "ok", (out.returncode, out.stdout, out.stderr)
+
+
+def test_size_limits_are_reported_before_any_gpu_work():
+    lib = binding.load()
+    out = ctypes.c_void_p()
+    # N = f*s must stay below 2^31 - block
+    p = binding.radial_mask_params(1 << 16, 1 << 15, 128, 1, 0, 1, 1, 0)
+    assert lib.radial_mask_build(ctypes.byref(p), None, ctypes.byref(out)) == -1
+    assert "token count" in binding.radial_last_error()
+    # more key blocks than the builder's bitmap holds (491 520)
+    p = binding.radial_mask_params(1000, 40000, 64, 1, 0, 1, 1, 0)
+    assert lib.radial_mask_build(ctypes.byref(p), None, ctypes.byref(out)) == -4
+    assert "key blocks" in binding.radial_last_error()
+    # sparsity knob outside its range, negative text-token count
+    p = binding.radial_mask_params(4, 64, 64, 1, 0, 40000, 1, 0)
+    assert lib.radial_mask_build(ctypes.byref(p), None, ctypes.byref(out)) == -1
+    p = binding.radial_mask_params(4, 64, 64, 1, 0, 1, 1, -3)
+    assert lib.radial_mask_build(ctypes.byref(p), None, ctypes.byref(out)) == -1
+    assert out.value is None
