@@ -1,0 +1,84 @@
+"""Seeded random geometries: GPU lists bit-exact against the brute-force scan; forward and
+backward (block-dense and token rule) against the oracle on small random shapes (run with -m gpu)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import attention as oa
+from oracle import build as obuild
+from oracle import mask as om
+from paper_2506_19852_amd import binding as rb
+
+from util import assert_close
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def test_random_masks_bit_exact():
+    rng = np.random.default_rng(20250619)
+    for case in range(60):
+        f = int(rng.integers(1, 80))
+        s = int(rng.integers(1, 400))
+        block = int(rng.choice([64, 128]))
+        sink = int(rng.integers(0, 3))
+        num, den = (int(rng.integers(1, 12)), int(rng.integers(1, 12))) if case % 2 else (1, 1)
+        extra = int(rng.integers(0, 300)) if case % 3 == 0 else 0
+        if (f * s + extra) > 14000:
+            s = max(1, 14000 // f)
+        print(f"random mask {case}: f={f} s={s} block={block} sink={sink} c={num}/{den} extra={extra}", flush=True)
+        bitmap, _ = obuild.mask_scan(f, s, block, sink, 0, None, num, den, extra)
+        want_ptr, want_idx = om.block_lists(bitmap)
+        m = rb.radial_mask_build(f, s, block, sink, rb.RADIAL_MASK_TRANSPOSE, width_num=num, width_den=den, extra_tokens=extra)
+        got_ptr, got_idx = rb.radial_mask_copy_to_host(m)
+        assert np.array_equal(got_ptr, want_ptr) and np.array_equal(got_idx, want_idx), case
+        t_ptr, t_idx = rb.radial_mask_copy_transpose_to_host(m)
+        wt_ptr, wt_idx = om.block_lists(np.ascontiguousarray(bitmap.T))
+        assert np.array_equal(t_ptr, wt_ptr) and np.array_equal(t_idx, wt_idx), case
+        m.free()
+
+
+def test_random_attention_shapes():
+    rng = np.random.default_rng(7)
+    g = torch.Generator(device="cpu").manual_seed(7)
+    for case in range(16):
+        exact = case % 2 == 1
+        f = int(rng.integers(1, 30))
+        s = int(rng.integers(64, 260)) if exact else int(rng.integers(1, 260))
+        block = int(rng.choice([64, 128]))
+        D = int(rng.choice([64, 128]))
+        sink = int(rng.integers(0, 3))
+        num, den = (int(rng.integers(1, 6)), int(rng.integers(1, 6))) if case % 4 >= 2 else (1, 1)
+        extra = int(rng.integers(0, 150)) if case % 3 == 0 else 0
+        if f * s > 2600:
+            f = max(1, 2600 // s)
+        N = f * s + extra
+        B, H = (2, 1) if case % 5 == 0 else (1, 2)
+        print(f"random attention {case}: f={f} s={s} block={block} D={D} sink={sink} c={num}/{den} extra={extra} "
+              f"token rule={exact} B={B} H={H}", flush=True)
+        q, k, v, do = ((torch.randn((B, H, N, D), generator=g)).to(torch.bfloat16).to(DEV) for _ in range(4))
+        scale = float(rng.uniform(0.05, 0.2))
+        flags = rb.RADIAL_MASK_TRANSPOSE | (rb.RADIAL_MASK_TOKEN_EXACT if exact else 0)
+        mask = rb.radial_mask_build(f, s, block, sink, flags, width_num=num, width_den=den, extra_tokens=extra)
+        out = torch.empty_like(q)
+        lse = torch.empty((B, H, N), dtype=torch.float32, device=DEV)
+        rb.radial_attn_fwd(q, k, v, out, lse, mask, scale)
+        ws = torch.empty(rb.radial_attn_bwd_workspace(B, H, N, D, mask), dtype=torch.uint8, device=DEV)
+        dq, dk, dv = (torch.full_like(q, float("nan")) for _ in range(3))
+        rb.radial_attn_bwd(q, k, v, out, do, lse, dq, dk, dv, mask, scale, ws)
+        torch.cuda.synchronize()
+        if exact:
+            vis = om.token_mask_rows_with_text(f, s, sink, np.arange(N), extra, num, den)
+        else:
+            bitmap, _ = obuild.mask_scan(f, s, block, sink, 0, None, num, den, extra)
+            vis = np.repeat(np.repeat(bitmap, block, axis=0), block, axis=1)[:N, :N]
+        for b in range(B):
+            for h in range(H):
+                qh, kh, vh, gh = (t[b, h].float().cpu().numpy() for t in (q, k, v, do))
+                ref_o, ref_l, _ = oa.attention_rows(qh, kh, vh, vis, scale)
+                assert_close(out[b, h].float().cpu().numpy(), ref_o, f"case {case} O")
+                assert np.allclose(lse[b, h].cpu().numpy(), ref_l, rtol=1e-4, atol=1e-4), case
+                ref = oa.attention_bwd_rows(qh, kh, vh, vis, scale, gh)[:3]
+                for got, want, nm in zip((dq, dk, dv), ref, ("dQ", "dK", "dV")):
+                    assert_close(got[b, h].float().cpu().numpy(), want, f"case {case} {nm}")
+        mask.free()
