@@ -40,7 +40,8 @@ typedef enum {
   RADIAL_EINVAL = -1,       /* NULL where a pointer is required, bad parameter value, unsorted list   */
   RADIAL_ENOMEM = -2,       /* host or device allocation failed                                      */
   RADIAL_EHIP = -3,         /* a HIP runtime call failed; radial_last_error() carries its message    */
-  RADIAL_EUNSUPPORTED = -4, /* block or head dimension outside {64, 128}                             */
+  RADIAL_EUNSUPPORTED = -4, /* block or head dimension outside {64, 128}; more blocks or listed pairs than
+                               the lists can index; token rule with frames shorter than 64 tokens   */
   RADIAL_ESHAPE = -5        /* tensor shape / stride / workspace does not match the mask or the call */
 } radial_status;
 
@@ -90,7 +91,8 @@ typedef struct radial_mask radial_mask;
 
 /* Builds the radial block lists with integer kernels on the GPU.  *out receives a new mask
  * that the caller releases with radial_mask_free.  Errors: EINVAL (NULL, f<1, s<1, sink<0,
- * unknown flag, N too large), EUNSUPPORTED (block), ENOMEM, EHIP. */
+ * extra_tokens<0, knob out of range, unknown flag, N too large), EUNSUPPORTED (block, more
+ * than 491 520 key blocks, more than 2^31-1 listed pairs, token rule with s < 64), ENOMEM, EHIP. */
 RADIAL_API int radial_mask_build(const radial_mask_params* params, void* hip_stream, radial_mask** out);
 
 /* A banded static mask: query token (i,k) may attend key token (j,l) iff j < sink_frames or
@@ -154,8 +156,9 @@ typedef struct {
  *   scale   : the 1/sqrt(d) of Eq. 2 (any positive finite value is accepted).
  * Inside a listed block pair every key with index < N is visible; with a mask built under
  * RADIAL_MASK_TOKEN_EXACT only the pairs the token rule allows are.  A query row with no
- * visible key gets out = 0 and lse = -inf.  Products run on bf16 MFMA with fp32 accumulation; the softmax is fp32; P is rounded to bf16 before P.V; out is rounded to
- * nearest-even bf16.  Allocates nothing.
+ * visible key gets out = 0 and lse = -inf.  Products run on bf16 MFMA with fp32 accumulation;
+ * the softmax is fp32; P is rounded to bf16 before P.V; out is rounded to nearest-even bf16.
+ * Allocates nothing (the call can be captured into a HIP graph).
  * Errors: EINVAL (NULL, scale), EUNSUPPORTED (D not 64/128), ESHAPE (N != mask n_tokens,
  * misaligned pointer/stride, B*H*n_blocks >= 2^31), EHIP. */
 RADIAL_API int radial_attn_fwd(int32_t B, int32_t H, int32_t N, int32_t D, radial_tensor q, radial_tensor k,
