@@ -70,6 +70,28 @@ def cpu_baseline(w, x, row_ptr, col_idx, budget_s=12.0):
             "sample": f"{done} of {nb} query blocks of head 0 ({w.name}), float64 numpy, {dt:.1f} s"}
 
 
+def load_balance(trace):
+    """Busy time per compute unit and per XCD from the per-workgroup records of one traced forward launch."""
+    import numpy as np
+    used = trace[:, 1] != 0
+    begin, end, where = trace[used, 0], trace[used, 1], trace[used, 2]
+    span = float(end.max() - begin.min())                  # ticks of the 100 MHz clock
+    xcc = (where >> 32) & 0xF
+    cu = xcc * 256 + ((where >> 8) & 0xFF)                 # XCD, shader engine / array, compute unit
+    busy = np.zeros(int(cu.max()) + 1)
+    np.add.at(busy, cu, (end - begin).astype(np.float64))
+    busy = busy[busy > 0]
+    last = np.zeros(8)
+    np.maximum.at(last, xcc, (end - begin.min()).astype(np.float64))
+    # two workgroups are resident per compute unit, so a fully busy unit shows 2 x span
+    occ = busy / (2.0 * span)
+    return {"workgroups": int(used.sum()), "compute_units_seen": int(busy.size),
+            "launch_span_ms": round(span / 1e5, 3),
+            "cu_busy_frac_min_mean_max": [round(float(occ.min()), 3), round(float(occ.mean()), 3), round(float(occ.max()), 3)],
+            "xcd_finish_frac_min_max": [round(float(last.min() / span), 3), round(float(last.max() / span), 3)],
+            "xcd_is_workgroup_id_mod_8": round(float(np.mean(xcc == (np.nonzero(used)[0] & 7))), 4)}
+
+
 def complexity_curve(frames_list, heads, args):
     """Forward time under the radial list and under the all-ones list as the video grows (frames
     of the 720p geometry, s = 3600): the empirical form of the paper's O(n log n) claim (Fig. 2,
@@ -218,7 +240,8 @@ def main():
         step(keep)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    kernel_ms = float(np.mean([e0.elapsed_time(e1) for (_, e0, e1) in keep]))
+    launch_ms = [e0.elapsed_time(e1) for (_, e0, e1) in keep]
+    kernel_ms = float(np.mean(launch_ms))
     row_ptr, col_idx = rb.radial_mask_copy_to_host(keep[0][0])
     for m, _, _ in keep:
         m.free()
@@ -243,6 +266,31 @@ def main():
     dense_ms = e0.elapsed_time(e1) / args.dense_steps
     dense.free()
 
+    # mask build alone (static mask: built once per video shape), host clock around a synchronised call
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    m = build_mask()
+    torch.cuda.synchronize()
+    mask_build_ms = (time.perf_counter() - t0) * 1e3
+
+    # load balance: one traced launch, {begin, end, where} per workgroup
+    trace = torch.zeros((rb.radial_attn_fwd_trace_records(w.B, w.H, m), 3), dtype=torch.int64, device=dev)
+    rb.radial_attn_fwd_trace(x["q"], x["k"], x["v"], out, lse, m, w.scale, trace)
+    torch.cuda.synchronize()
+    m.free()
+    balance = load_balance(trace.cpu().numpy())
+    del trace
+
+    # the matrix pipes alone, at the clock the chip sustains: dependent MFMAs on registers
+    probe_iters = 20000
+    rb.radial_probe_mfma_bf16(probe_iters)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    probe_flops = rb.radial_probe_mfma_bf16(probe_iters)
+    e1.record()
+    torch.cuda.synchronize()
+    probe_tflops = probe_flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+
     achieved = fwd_flops / (kernel_ms * 1e-3) / 1e12
     result = {
         "metric": "effective TFLOP/s on computed blocks + speedup vs dense attn at same N, 1 GPU",
@@ -256,12 +304,16 @@ def main():
                    "width_scale": f"{width_num}/{width_den}", "pattern": args.pattern,
                    "block_sparsity": round(1.0 - float(row_ptr[-1]) / float((row_ptr.size - 1) ** 2), 4)},
         "fwd_kernel_ms": round(kernel_ms, 3),
+        "fwd_kernel_ms_median": round(float(np.median(launch_ms)), 3), "fwd_kernel_ms_min": round(float(np.min(launch_ms)), 3),
+        "mask_build_ms": round(mask_build_ms, 3),
+        "mfma_probe_tflops": round(probe_tflops, 1),
+        "load_balance": balance,
         "dense_fwd_kernel_ms": round(dense_ms, 3),
         "dense_tflops": round(dense_flops / (dense_ms * 1e-3) / 1e12, 2),
         "speedup_vs_dense": round(dense_ms / kernel_ms, 3),
         "block_ratio_dense_over_radial": round(dense_flops / fwd_flops, 3),
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if (width_num == width_den and not args.token_exact and args.pattern == "radial") else None,
+                     "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "frac_of_mfma_probe": round(achieved / probe_tflops, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if (width_num == width_den and not args.token_exact and args.pattern == "radial") else None,
                      "kernel": "radial_fwd_kernel", "flops_per_launch": fwd_flops},
     }
     if not args.no_cpu_baseline:

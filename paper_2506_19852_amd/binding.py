@@ -21,6 +21,7 @@ EXPORTS = (
     "radial_last_error", "radial_mask_build", "radial_mask_build_banded", "radial_mask_build_dense", "radial_mask_from_csr",
     "radial_mask_info", "radial_mask_copy_to_host", "radial_mask_copy_transpose_to_host",
     "radial_mask_free", "radial_attn_fwd", "radial_attn_bwd_workspace", "radial_attn_bwd",
+    "radial_attn_fwd_trace_records", "radial_attn_fwd_trace", "radial_probe_mfma_bf16",
 )
 
 
@@ -70,13 +71,17 @@ def load():
     lib.radial_mask_free.restype = None
     lib.radial_attn_fwd.argtypes = [c_int32, c_int32, c_int32, c_int32, radial_tensor, radial_tensor, radial_tensor,
                                     radial_tensor, c_void_p, c_void_p, c_float, c_void_p]
+    lib.radial_attn_fwd_trace.argtypes = lib.radial_attn_fwd.argtypes + [c_void_p, ctypes.c_int64]
+    lib.radial_attn_fwd_trace_records.argtypes = [c_int32, c_int32, c_void_p]
+    lib.radial_attn_fwd_trace_records.restype = ctypes.c_int64
+    lib.radial_probe_mfma_bf16.argtypes = [ctypes.c_int64, c_void_p, ctypes.POINTER(ctypes.c_double)]
     lib.radial_attn_bwd_workspace.argtypes = [c_int32, c_int32, c_int32, c_int32, c_void_p]
     lib.radial_attn_bwd_workspace.restype = c_size_t
     lib.radial_attn_bwd.argtypes = [c_int32, c_int32, c_int32, c_int32] + [radial_tensor] * 5 + [c_void_p] + \
         [radial_tensor] * 3 + [c_void_p, c_float, c_void_p, c_size_t, c_void_p]
     for name in EXPORTS:
         fn = getattr(lib, name)
-        if name not in ("radial_last_error", "radial_mask_free", "radial_attn_bwd_workspace"):
+        if name not in ("radial_last_error", "radial_mask_free", "radial_attn_bwd_workspace", "radial_attn_fwd_trace_records"):
             fn.restype = ctypes.c_int
     _lib = lib
     return lib
@@ -200,6 +205,29 @@ def radial_attn_fwd(q, k, v, out, lse, mask: RadialMask, scale: float, stream=No
         lse_ptr = c_void_p(lse.data_ptr())
     _check(load().radial_attn_fwd(B, H, N, D, _tensor(q, "q"), _tensor(k, "k"), _tensor(v, "v"), _tensor(out, "out"),
                                   lse_ptr, mask.handle, c_float(scale), _stream_ptr(stream)))
+
+
+def radial_attn_fwd_trace_records(B: int, H: int, mask: RadialMask) -> int:
+    return int(load().radial_attn_fwd_trace_records(B, H, mask.handle))
+
+
+def radial_attn_fwd_trace(q, k, v, out, lse, mask: RadialMask, scale: float, trace, stream=None):
+    """radial_attn_fwd plus one {begin, end, where} record per workgroup in trace (zeroed CUDA int64 [records, 3])."""
+    import torch
+    B, H, N, D = q.shape
+    if trace.dtype != torch.int64 or not trace.is_cuda or not trace.is_contiguous() or trace.dim() != 2 or trace.shape[1] != 3:
+        raise ValueError("trace must be a contiguous CUDA int64 tensor [records, 3]")
+    lse_ptr = c_void_p(lse.data_ptr()) if lse is not None else None
+    _check(load().radial_attn_fwd_trace(B, H, N, D, _tensor(q, "q"), _tensor(k, "k"), _tensor(v, "v"), _tensor(out, "out"),
+                                        lse_ptr, mask.handle, c_float(scale), _stream_ptr(stream),
+                                        c_void_p(trace.data_ptr()), trace.shape[0]))
+
+
+def radial_probe_mfma_bf16(iterations: int, stream=None) -> float:
+    """Launches the MFMA-only probe kernel; returns the floating-point operations it performs."""
+    flops = ctypes.c_double(0.0)
+    _check(load().radial_probe_mfma_bf16(iterations, _stream_ptr(stream), ctypes.byref(flops)))
+    return flops.value
 
 
 def radial_attn_bwd_workspace(B: int, H: int, N: int, D: int, mask: RadialMask) -> int:

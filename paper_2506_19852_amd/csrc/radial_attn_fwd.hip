@@ -71,17 +71,21 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_fwd_kernel(const FwdArgs a)
   const int lq = lane & 31;   // query column / K row inside a 32-tile
   const int g = lane >> 5;    // which half of the 16-wide MFMA k-slice this lane feeds
 
-  // Workgroup -> work item.  Consecutive workgroup ids go to different XCDs; XCD x owns the
-  // query blocks [slice[x], slice[x+1]) and walks them head after head, so all XCDs work on
-  // the same head at the same time (its K/V stay in the shared last-level cache) and
-  // neighbouring workgroups of an XCD share K/V tiles in that XCD's L2.
+  // Workgroup -> work item.  Consecutive workgroup ids go to different XCDs.  The query blocks are
+  // cut into 8 slices of equal list weight; for head bh, XCD x takes slice (x + bh) mod 8 and the
+  // XCDs move from head to head together, so all of them work on the same head at the same time
+  // (its K/V stay in the shared last-level cache), neighbouring workgroups of an XCD share K/V
+  // tiles in that XCD's L2, and every XCD gets every slice equally often (slices of equal weight
+  // do not take exactly equal time).
+  const uint64_t t_begin = a.wg_trace ? __builtin_amdgcn_s_memrealtime() : 0;
   const int32_t xcd = blockIdx.x & 7;
-  const int32_t s0 = a.slice[xcd];
-  const int32_t slice_len = a.slice[xcd + 1] - s0;
   const int64_t idx = blockIdx.x >> 3;
-  if (slice_len <= 0 || idx >= (int64_t)slice_len * a.B * a.H) return;
-  const int32_t bh = (int32_t)(idx / slice_len);
-  const int32_t qb = s0 + (int32_t)(idx % slice_len);
+  const int32_t bh = (int32_t)(idx / a.max_slice);
+  const int32_t pos = (int32_t)(idx % a.max_slice);
+  const int32_t sl = (xcd + bh) & 7;
+  const int32_t s0 = a.slice[sl];
+  if (pos >= a.slice[sl + 1] - s0) return;
+  const int32_t qb = s0 + pos;
   const int32_t b = bh / a.H, h = bh % a.H;
 
   const __bf16* qp = (const __bf16*)a.q.ptr + (int64_t)b * a.q.sb + (int64_t)h * a.q.sh;
@@ -341,6 +345,15 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_fwd_kernel(const FwdArgs a)
       a.lse[idx] = l_tot > 0.f ? m_run * a.scale + __logf(l_tot) : -INFINITY;
     }
   }
+  if (a.wg_trace != nullptr && threadIdx.x == 0) {
+    // hardware id registers: which XCD, shader engine and compute unit this workgroup ran on
+    constexpr int kHwId = 4, kXccId = 20, kAllBits = 31 << 11;
+    const uint64_t where = ((uint64_t)__builtin_amdgcn_s_getreg(kXccId | kAllBits) << 32) | (uint32_t)__builtin_amdgcn_s_getreg(kHwId | kAllBits);
+    uint64_t* rec = a.wg_trace + 3 * (int64_t)blockIdx.x;
+    rec[0] = t_begin;
+    rec[1] = __builtin_amdgcn_s_memrealtime();
+    rec[2] = where;
+  }
 }
 
 template <int D, int BLK>
@@ -357,6 +370,53 @@ int launch(const FwdArgs& a, hipStream_t stream) {
 }
 
 }  // namespace
+
+int64_t fwd_grid(const FwdArgs& a) { return 8LL * a.B * a.H * a.max_slice; }
+
+namespace {
+// 4 waves per SIMD, each a chain of dependent 32x32x16 bf16 MFMAs on registers: the rate the
+// matrix pipes sustain at the clock the chip holds, with no memory traffic at all.
+__global__ void __launch_bounds__(1024) mfma_probe_kernel(int64_t iters, float* sink) {
+  // operands: pseudo-random bf16 values in (-2, 2), four different A and B registers in turn, so
+  // the multipliers see changing bits as they do on real data
+  bf16x8 x[4], y[4];
+  uint32_t r = threadIdx.x * 2654435761u + 12345u;
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      r = r * 1664525u + 1013904223u;
+      x[j][i] = (__bf16)((float)(int)(r >> 16 & 0xFFFF) * (1.f / 16384.f) - 2.f);
+      r = r * 1664525u + 1013904223u;
+      y[j][i] = (__bf16)((float)(int)(r >> 16 & 0xFFFF) * (1.f / 16384.f) - 2.f);
+    }
+  f32x16 acc[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
+  for (int64_t it = 0; it < iters; it += 4) {  // iters is a multiple of 4
+#pragma unroll
+    for (int rot = 0; rot < 4; ++rot)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x[j], y[(j + rot) & 3], acc[j], 0, 0, 0);
+  }
+  float t = 0.f;
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) t += acc[j][e];
+  if (t == 0.12345f && sink != nullptr) sink[0] = t;  // keeps the chains alive; sink is null in every launch
+}
+constexpr int kProbeGrid = 256 * 8;  // 8 workgroups of 16 waves per compute unit
+}  // namespace
+
+int launch_mfma_probe(int64_t iters, hipStream_t stream, double* flops_out) {
+  mfma_probe_kernel<<<dim3(kProbeGrid), dim3(1024), 0, stream>>>(iters, nullptr);
+  RADIAL_HIP_TRY(hipGetLastError());
+  if (flops_out) *flops_out = (double)kProbeGrid * 16.0 * (double)iters * 4.0 * (2.0 * 32 * 32 * 16);
+  return RADIAL_OK;
+}
 
 int launch_fwd(int D, int block, const FwdArgs& a, hipStream_t stream) {
   if (D == 128 && block == 128) return launch<128, 128>(a, stream);

@@ -86,9 +86,15 @@ struct FwdArgs {
   int32_t B, H, N, n_blocks;
   float scale;
   TokenRule rule;
+  uint64_t* wg_trace;  // null, or [grid][3]: begin, end (100 MHz clock), where the workgroup ran
 };
 
 int launch_fwd(int D, int block, const FwdArgs& a, hipStream_t stream);
+// Workgroups one forward launch of this shape starts (the number of trace records).
+int64_t fwd_grid(const FwdArgs& a);
+// Launches a kernel that only issues dependent bf16 MFMAs from registers; *flops_out (host)
+// receives the floating-point operations it performs.
+int launch_mfma_probe(int64_t iters, hipStream_t stream, double* flops_out);
 
 struct BwdArgs {
   TensorArg q, k, v, o, dout, dq, dk, dv;
