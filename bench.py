@@ -66,8 +66,10 @@ def cpu_baseline(w, x, row_ptr, col_idx, budget_s=12.0):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         cores = os.cpu_count() or 1
+    total = effective_flops(row_ptr, col_idx, w.N, w.block, w.D, w.B * w.H)
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"{done} of {nb} query blocks of head 0 ({w.name}), float64 numpy, {dt:.1f} s"}
+            "sample": f"{done} of {nb} query blocks of head 0 ({w.name}), float64 numpy, {dt:.1f} s",
+            "sampled_fraction_of_flops": flops / total, "extrapolated_full_forward_s": dt * total / flops}
 
 
 def load_balance(trace):
