@@ -170,6 +170,9 @@ def main():
     ap.add_argument("--pattern", default="radial",
                     help="mask: radial (default), or a banded comparison mask: spatial:W (frames), temporal:H (positions), "
                          "sliding:W:H, harmonic")
+    ap.add_argument("--fp8-scores", action="store_true",
+                    help="forward with Q and K quantised to E4M3 per 128-token block (scores on the 8-bit matrix "
+                         "instruction); a reduced-precision extra, never the headline number")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain device copy of q (known size) so a rocprofv3 --pmc run can scale FETCH_SIZE/WRITE_SIZE")
     ap.add_argument("--curve-frames", default=None, metavar="F1,F2,...",
@@ -213,11 +216,34 @@ def main():
                  "sliding": patterns.sliding_window, "harmonic": patterns.harmonic_decay}[kind](w.frames, w.tokens_per_frame, *par)
         return rb.radial_mask_build_banded(w.frames, w.tokens_per_frame, w.block, 1, table, flags)
 
+    quant = None
+    if args.fp8_scores:
+        if w.backward or args.token_exact or w.block != 128 or w.D != 128:
+            print("--fp8-scores: forward only, block 128, D 128, listed blocks dense", file=sys.stderr)
+            sys.exit(2)
+        nb = (w.N + w.block - 1) // w.block
+        quant = {"qc": torch.empty(x["q"].shape, dtype=torch.uint8, device=dev), "kc": torch.empty(x["k"].shape, dtype=torch.uint8, device=dev),
+                 "qs": torch.empty((w.B, w.H, nb), dtype=torch.float32, device=dev), "ks": torch.empty((w.B, w.H, nb), dtype=torch.float32, device=dev)}
+        for _ in range(2):      # second pass timed
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            rb.radial_quantize_fp8(x["q"], w.block, quant["qc"], quant["qs"])
+            rb.radial_quantize_fp8(x["k"], w.block, quant["kc"], quant["ks"])
+            e1.record()
+            torch.cuda.synchronize()
+        quant["ms"] = e0.elapsed_time(e1)
+
+    def forward(m, lse_out):
+        if quant is not None:
+            rb.radial_attn_fwd_fp8(quant["qc"], quant["qs"], quant["kc"], quant["ks"], x["v"], out, lse_out, m, w.scale)
+        else:
+            rb.radial_attn_fwd(x["q"], x["k"], x["v"], out, lse_out, m, w.scale)
+
     def step(keep=None):
         m = build_mask()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        rb.radial_attn_fwd(x["q"], x["k"], x["v"], out, lse, m, w.scale)
+        forward(m, lse)
         e1.record()
         if w.backward:
             nonlocal ws
@@ -257,12 +283,12 @@ def main():
     dense = rb.radial_mask_build_dense(w.N, w.block)
     dptr, didx = rb.radial_mask_copy_to_host(dense)
     dense_flops = effective_flops(dptr, didx, w.N, w.block, w.D, w.B * w.H)
-    rb.radial_attn_fwd(x["q"], x["k"], x["v"], out, None, dense, w.scale)
+    forward(dense, None)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(args.dense_steps):
-        rb.radial_attn_fwd(x["q"], x["k"], x["v"], out, None, dense, w.scale)
+        forward(dense, None)
     e1.record()
     torch.cuda.synchronize()
     dense_ms = e0.elapsed_time(e1) / args.dense_steps
@@ -276,12 +302,14 @@ def main():
     mask_build_ms = (time.perf_counter() - t0) * 1e3
 
     # load balance: one traced launch, {begin, end, where} per workgroup
-    trace = torch.zeros((rb.radial_attn_fwd_trace_records(w.B, w.H, m), 3), dtype=torch.int64, device=dev)
-    rb.radial_attn_fwd_trace(x["q"], x["k"], x["v"], out, lse, m, w.scale, trace)
-    torch.cuda.synchronize()
+    balance = None
+    if quant is None:
+        trace = torch.zeros((rb.radial_attn_fwd_trace_records(w.B, w.H, m), 3), dtype=torch.int64, device=dev)
+        rb.radial_attn_fwd_trace(x["q"], x["k"], x["v"], out, lse, m, w.scale, trace)
+        torch.cuda.synchronize()
+        balance = load_balance(trace.cpu().numpy())
+        del trace
     m.free()
-    balance = load_balance(trace.cpu().numpy())
-    del trace
 
     # the matrix pipes alone, at the clock the chip sustains: dependent MFMAs on registers
     probe_iters = 20000
@@ -298,7 +326,7 @@ def main():
         "metric": "effective TFLOP/s on computed blocks + speedup vs dense attn at same N, 1 GPU",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": "fp8_e4m3 scores, bf16 PV" if quant is not None else "bf16", "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "D": w.D, "frames": w.frames,
                    "tokens_per_frame": w.tokens_per_frame, "block": w.block, "sink_frames": 1,
                    "listed_block_pairs": int(row_ptr[-1]), "pass": "fwd+bwd" if w.backward else "fwd",
@@ -318,6 +346,11 @@ def main():
                      "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "frac_of_mfma_probe": round(achieved / probe_tflops, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if (width_num == width_den and not args.token_exact and args.pattern == "radial") else None,
                      "kernel": "radial_fwd_kernel", "flops_per_launch": fwd_flops},
     }
+    if quant is not None:
+        result["quantize_q_and_k_ms"] = round(quant["ms"], 3)
+        result["roofline"]["kernel"] = "radial_fwd_fp8_kernel"
+        result["roofline"]["traffic"] = None
+        result["roofline"]["note"] = "half of the flops run on the 8-bit matrix instruction; peak and frac are still the bf16 figures"
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, x, row_ptr, col_idx)
     print(json.dumps(result))

@@ -181,6 +181,32 @@ RADIAL_API int radial_attn_bwd(int32_t B, int32_t H, int32_t N, int32_t D, radia
                     radial_tensor dq, radial_tensor dk, radial_tensor dv, const radial_mask* mask,
                     float scale, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* ---- 8-bit scores (optional) -------------------------------------------------------------------
+ *
+ * The paper defines no quantisation (Sec. 2 and Sec. 6 call the method orthogonal to quantised
+ * attention kernels); this scheme is the library's own.  Q and K are cut into blocks of `block`
+ * consecutive tokens of one (batch, head); a block is stored as E4M3 codes (OCP 8-bit floating
+ * point: 4 exponent bits, bias 7, 3 mantissa bits, largest value 448, round to nearest even) of
+ * x / scale with scale = amax / 448 (1 for an all-zero block), all in float32.
+ *
+ * radial_quantize_fp8: x is a [B, H, N, D] bf16 tensor (strided like q), D a multiple of 8;
+ * codes (device, B*H*N*D bytes, contiguous [B, H, N, D], 16-byte aligned) and scales (device,
+ * B*H*ceil(N/block) floats, [B, H, block index]) are written.  Errors: RADIAL_EINVAL (NULL,
+ * sizes < 1), RADIAL_EUNSUPPORTED (D), RADIAL_ESHAPE (strides, alignment), RADIAL_EHIP.
+ *
+ * radial_attn_fwd_fp8 is radial_attn_fwd (Eq. 2 on the listed blocks, listed blocks dense) with
+ * the scores computed from such codes: S = (q codes . k codes) * q scale * k scale on the 8-bit
+ * matrix instruction; the softmax, P (bf16) and the product with V (bf16) are unchanged.  The
+ * codes must have been made with block = the mask's block.  Only D = 128 with block 128, and
+ * not for masks with RADIAL_MASK_TOKEN_EXACT (RADIAL_EUNSUPPORTED otherwise); other errors as
+ * radial_attn_fwd.  Allocates nothing. */
+RADIAL_API int radial_quantize_fp8(int32_t B, int32_t H, int32_t N, int32_t D, radial_tensor x, int32_t block,
+                                   uint8_t* codes, float* scales, void* hip_stream);
+RADIAL_API int radial_attn_fwd_fp8(int32_t B, int32_t H, int32_t N, int32_t D, const uint8_t* q_codes,
+                                   const float* q_scales, const uint8_t* k_codes, const float* k_scales,
+                                   radial_tensor v, radial_tensor out, float* lse, const radial_mask* mask,
+                                   float scale, void* hip_stream);
+
 /* ---- measurement aids (no part of the method; used by the benchmark) -------------------------
  *
  * radial_attn_fwd_trace is radial_attn_fwd plus one record per workgroup of the launch, for

@@ -22,6 +22,7 @@ EXPORTS = (
     "radial_mask_info", "radial_mask_copy_to_host", "radial_mask_copy_transpose_to_host",
     "radial_mask_free", "radial_attn_fwd", "radial_attn_bwd_workspace", "radial_attn_bwd",
     "radial_attn_fwd_trace_records", "radial_attn_fwd_trace", "radial_probe_mfma_bf16",
+    "radial_quantize_fp8", "radial_attn_fwd_fp8",
 )
 
 
@@ -75,6 +76,9 @@ def load():
     lib.radial_attn_fwd_trace_records.argtypes = [c_int32, c_int32, c_void_p]
     lib.radial_attn_fwd_trace_records.restype = ctypes.c_int64
     lib.radial_probe_mfma_bf16.argtypes = [ctypes.c_int64, c_void_p, ctypes.POINTER(ctypes.c_double)]
+    lib.radial_quantize_fp8.argtypes = [c_int32, c_int32, c_int32, c_int32, radial_tensor, c_int32, c_void_p, c_void_p, c_void_p]
+    lib.radial_attn_fwd_fp8.argtypes = [c_int32, c_int32, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
+                                        radial_tensor, radial_tensor, c_void_p, c_void_p, c_float, c_void_p]
     lib.radial_attn_bwd_workspace.argtypes = [c_int32, c_int32, c_int32, c_int32, c_void_p]
     lib.radial_attn_bwd_workspace.restype = c_size_t
     lib.radial_attn_bwd.argtypes = [c_int32, c_int32, c_int32, c_int32] + [radial_tensor] * 5 + [c_void_p] + \
@@ -228,6 +232,42 @@ def radial_probe_mfma_bf16(iterations: int, stream=None) -> float:
     flops = ctypes.c_double(0.0)
     _check(load().radial_probe_mfma_bf16(iterations, _stream_ptr(stream), ctypes.byref(flops)))
     return flops.value
+
+
+def radial_quantize_fp8(x, block: int, codes, scales, stream=None):
+    """codes (uint8 [B,H,N,D]) and scales (float32 [B,H,ceil(N/block)]) <- per-block E4M3 quantisation of x (bf16)."""
+    import torch
+    B, H, N, D = x.shape
+    nb = (N + block - 1) // block
+    if codes.dtype != torch.uint8 or not codes.is_cuda or not codes.is_contiguous() or tuple(codes.shape) != (B, H, N, D):
+        raise ValueError("codes must be a contiguous CUDA uint8 tensor [B, H, N, D]")
+    if scales.dtype != torch.float32 or not scales.is_cuda or not scales.is_contiguous() or tuple(scales.shape) != (B, H, nb):
+        raise ValueError("scales must be a contiguous CUDA float32 tensor [B, H, ceil(N/block)]")
+    _check(load().radial_quantize_fp8(B, H, N, D, _tensor(x, "x"), block, c_void_p(codes.data_ptr()),
+                                      c_void_p(scales.data_ptr()), _stream_ptr(stream)))
+
+
+def radial_attn_fwd_fp8(q_codes, q_scales, k_codes, k_scales, v, out, lse, mask: RadialMask, scale: float, stream=None):
+    """radial_attn_fwd with the scores computed from E4M3 codes of q and k (see radial_quantize_fp8)."""
+    import torch
+    B, H, N, D = v.shape
+    nb = (N + 127) // 128
+    for t, nm in ((q_codes, "q_codes"), (k_codes, "k_codes")):
+        if t.dtype != torch.uint8 or not t.is_cuda or not t.is_contiguous() or tuple(t.shape) != (B, H, N, D):
+            raise ValueError(f"{nm} must be a contiguous CUDA uint8 tensor [B, H, N, D]")
+    for t, nm in ((q_scales, "q_scales"), (k_scales, "k_scales")):
+        if t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous() or tuple(t.shape) != (B, H, nb):
+            raise ValueError(f"{nm} must be a contiguous CUDA float32 tensor [B, H, ceil(N/128)]")
+    if tuple(out.shape) != (B, H, N, D):
+        raise ValueError("out has the wrong shape")
+    lse_ptr = None
+    if lse is not None:
+        if lse.dtype != torch.float32 or not lse.is_cuda or not lse.is_contiguous() or tuple(lse.shape) != (B, H, N):
+            raise ValueError("lse must be a contiguous CUDA float32 tensor [B, H, N]")
+        lse_ptr = c_void_p(lse.data_ptr())
+    _check(load().radial_attn_fwd_fp8(B, H, N, D, c_void_p(q_codes.data_ptr()), c_void_p(q_scales.data_ptr()),
+                                      c_void_p(k_codes.data_ptr()), c_void_p(k_scales.data_ptr()), _tensor(v, "v"),
+                                      _tensor(out, "out"), lse_ptr, mask.handle, c_float(scale), _stream_ptr(stream)))
 
 
 def radial_attn_bwd_workspace(B: int, H: int, N: int, D: int, mask: RadialMask) -> int:

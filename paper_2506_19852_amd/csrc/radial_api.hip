@@ -120,3 +120,37 @@ extern "C" int radial_attn_bwd(int32_t B, int32_t H, int32_t N, int32_t D, radia
   a.rule = make_token_rule(mask);
   return launch_bwd(D, mask->block, a, (hipStream_t)hip_stream);
 }
+
+extern "C" int radial_quantize_fp8(int32_t B, int32_t H, int32_t N, int32_t D, radial_tensor x, int32_t block,
+                                   uint8_t* codes, float* scales, void* hip_stream) {
+  if (B < 1 || H < 1 || N < 1) return fail(RADIAL_EINVAL, "B, H, N must be >= 1");
+  if (D < 8 || (D & 7)) return fail(RADIAL_EUNSUPPORTED, "head dimension must be a positive multiple of 8 (got %d)", D);
+  if (block < 1) return fail(RADIAL_EINVAL, "block must be >= 1");
+  if (int rc = check_tensor("x", x, D)) return rc;
+  if (!codes || !scales) return fail(RADIAL_EINVAL, "codes or scales is NULL");
+  if ((uintptr_t)codes & 15u) return fail(RADIAL_ESHAPE, "codes is not 16-byte aligned");
+  return launch_quantize_fp8(B, H, N, D, arg(x), block, codes, scales, (hipStream_t)hip_stream);
+}
+
+extern "C" int radial_attn_fwd_fp8(int32_t B, int32_t H, int32_t N, int32_t D, const uint8_t* q_codes, const float* q_scales,
+                                   const uint8_t* k_codes, const float* k_scales, radial_tensor v, radial_tensor out,
+                                   float* lse, const radial_mask* mask, float scale, void* hip_stream) {
+  if (int rc = check_call(B, H, N, D, mask, scale)) return rc;
+  if (D != 128 || mask->block != 128) return fail(RADIAL_EUNSUPPORTED, "8-bit scores need head dimension 128 and block 128");
+  if (mask->flags & RADIAL_MASK_TOKEN_EXACT) return fail(RADIAL_EUNSUPPORTED, "8-bit scores do not apply the token rule inside blocks");
+  if (!q_codes || !k_codes || !q_scales || !k_scales) return fail(RADIAL_EINVAL, "codes or scales is NULL");
+  if (((uintptr_t)q_codes | (uintptr_t)k_codes) & 15u) return fail(RADIAL_ESHAPE, "codes are not 16-byte aligned");
+  if (int rc = check_tensor("v", v, D)) return rc;
+  if (int rc = check_tensor("out", out, D)) return rc;
+  Fp8FwdArgs a;
+  a.q8 = q_codes; a.k8 = k_codes; a.q_scale = q_scales; a.k_scale = k_scales;
+  a.v = arg(v); a.o = arg(out);
+  a.lse = lse;
+  a.row_ptr = mask->d_row_ptr;
+  a.col_idx = mask->d_col_idx;
+  a.slice = mask->d_slice;
+  a.max_slice = mask->max_slice;
+  a.B = B; a.H = H; a.N = N; a.n_blocks = mask->n_blocks;
+  a.scale = scale;
+  return launch_fwd_fp8(a, (hipStream_t)hip_stream);
+}

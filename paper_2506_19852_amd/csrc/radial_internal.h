@@ -96,6 +96,26 @@ int64_t fwd_grid(const FwdArgs& a);
 // receives the floating-point operations it performs.
 int launch_mfma_probe(int64_t iters, hipStream_t stream, double* flops_out);
 
+// 8-bit scores: Q and K as E4M3 codes ([B, H, N, D] bytes, contiguous) with one scale per
+// (batch, head, block of tokens).
+struct Fp8FwdArgs {
+  const uint8_t* q8;
+  const uint8_t* k8;
+  const float* q_scale;  // [B, H, n_blocks]
+  const float* k_scale;
+  TensorArg v, o;
+  float* lse;  // may be null
+  const int32_t* row_ptr;
+  const int32_t* col_idx;
+  const int32_t* slice;
+  int32_t max_slice;
+  int32_t B, H, N, n_blocks;
+  float scale;
+};
+int launch_fwd_fp8(const Fp8FwdArgs& a, hipStream_t stream);
+int launch_quantize_fp8(int32_t B, int32_t H, int32_t N, int32_t D, const TensorArg& x, int32_t block, uint8_t* codes,
+                        float* scales, hipStream_t stream);
+
 struct BwdArgs {
   TensorArg q, k, v, o, dout, dq, dk, dv;
   const float* lse;
