@@ -97,3 +97,44 @@ def test_8bit_forward_refuses_what_it_does_not_support():
         rb.radial_attn_fwd_fp8(qc, qs, qc, qs, v, torch.empty_like(v), None, m, 0.1)
     assert e.value.code == -4          # RADIAL_EUNSUPPORTED
     m.free()
+
+
+def test_8bit_forward_at_the_benchmark_workload_sampled_blocks():
+    """cfg3 in the launch configuration `bench.py --fp8-scores` times: sampled query blocks of two heads."""
+    from paper_2506_19852_amd import workloads as wl
+    from util import assert_close, oracle_fwd_block, sample_qblocks
+    w = wl.WORKLOADS["cfg3_hunyuan720p"]
+    f, s, block = w.frames, w.tokens_per_frame, w.block
+    x = {nm: wl.make_tensor(w, nm, "cuda:0") for nm in ("q", "k", "v")}
+    nb = (w.N + block - 1) // block
+    m = rb.radial_mask_build(f, s, block, 1, 0)
+    row_ptr, _ = rb.radial_mask_copy_to_host(m)
+    qc = torch.empty(x["q"].shape, dtype=torch.uint8, device="cuda")
+    kc = torch.empty_like(qc)
+    qs = torch.empty((w.B, w.H, nb), dtype=torch.float32, device="cuda")
+    ks = torch.empty_like(qs)
+    rb.radial_quantize_fp8(x["q"], block, qc, qs)
+    rb.radial_quantize_fp8(x["k"], block, kc, ks)
+    out = torch.empty_like(x["q"])
+    lse = torch.empty((w.B, w.H, w.N), dtype=torch.float32, device="cuda")
+    rb.radial_attn_fwd_fp8(qc, qs, kc, ks, x["v"], out, lse, m, w.scale)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all() and torch.isfinite(lse).all()
+    qblocks = sample_qblocks(nb, np.diff(row_ptr), s, block, 24, w.seed)
+    worst = 0.0
+    for h in (0, 23):
+        qn, kn, vn = (x[nm][0, h].float().cpu().numpy() for nm in ("q", "k", "v"))
+        qcodes, qscales = quant.quantize_blocks(qn, block)
+        kcodes, kscales = quant.quantize_blocks(kn, block)
+        assert np.array_equal(qc[0, h].cpu().numpy(), qcodes) and np.array_equal(ks[0, h].cpu().numpy(), kscales)
+        qd, kd = quant.dequantize_blocks(qcodes, qscales, block), quant.dequantize_blocks(kcodes, kscales, block)
+        oh, lh = out[0, h].float().cpu().numpy(), lse[0, h].cpu().numpy()
+        for qb in qblocks:
+            bm, _ = obuild.mask_scan(f, s, block, 1, qb, qb + 1)
+            ref_o, ref_l = oracle_fwd_block(qd, kd, vn, bm[0], qb, block, w.scale)
+            r0 = qb * block
+            err, _ = assert_close(oh[r0:r0 + ref_o.shape[0]], ref_o, f"fp8 cfg3 h{h} qb{qb} O")
+            assert np.allclose(lh[r0:r0 + ref_o.shape[0]], ref_l, rtol=1e-4, atol=1e-4), f"fp8 cfg3 h{h} qb{qb} LSE"
+            worst = max(worst, err)
+    print(f"fp8 cfg3: {len(qblocks)} query blocks x 2 heads checked, max |err| {worst:.3e}", flush=True)
+    m.free()
