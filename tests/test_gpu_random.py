@@ -72,6 +72,11 @@ def test_random_attention_shapes():
         else:
             bitmap, _ = obuild.mask_scan(f, s, block, sink, 0, None, num, den, extra)
             vis = np.repeat(np.repeat(bitmap, block, axis=0), block, axis=1)[:N, :N]
+        # Logits have standard deviation scale*sqrt(D) here; well above 1 the softmax rows are peaked,
+        # gradients reach several units, and the rounding of dS to bf16 puts errors of
+        # 2^-9 * (largest terms of the row) on every element of that row, however small the
+        # element itself is: the absolute term then scales with max|ref| (as for the stress inputs).
+        peaked = scale * np.sqrt(D) > 1.25
         for b in range(B):
             for h in range(H):
                 qh, kh, vh, gh = (t[b, h].float().cpu().numpy() for t in (q, k, v, do))
@@ -80,5 +85,5 @@ def test_random_attention_shapes():
                 assert np.allclose(lse[b, h].cpu().numpy(), ref_l, rtol=1e-4, atol=1e-4), case
                 ref = oa.attention_bwd_rows(qh, kh, vh, vis, scale, gh)[:3]
                 for got, want, nm in zip((dq, dk, dv), ref, ("dQ", "dK", "dV")):
-                    assert_close(got[b, h].float().cpu().numpy(), want, f"case {case} {nm}")
+                    assert_close(got[b, h].float().cpu().numpy(), want, f"case {case} {nm}", scaled_atol=peaked)
         mask.free()
