@@ -90,7 +90,7 @@ __global__ void __launch_bounds__(256) quantize_fp8_kernel(TensorArg x, uint8_t*
   }
 }
 
-__global__ void __launch_bounds__(kThreads, 2) radial_fwd_fp8_kernel(const Fp8FwdArgs a) {
+__global__ void __launch_bounds__(kThreads, 3) radial_fwd_fp8_kernel(const Fp8FwdArgs a) {
   // [stage buffer][K8 tile, V tile]
   __shared__ __attribute__((aligned(1024))) char lds[2 * kBufBytes];
   const uint32_t lds_base = lds_address(lds);
