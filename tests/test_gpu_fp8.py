@@ -48,7 +48,8 @@ def test_quantiser_reads_strided_tensors():
         assert np.array_equal(codes[0, h].cpu().numpy(), want_c) and np.array_equal(scales[0, h].cpu().numpy(), want_s)
 
 
-@pytest.mark.parametrize("f, s, sink, qscale", [(6, 200, 1, 1.0), (5, 333, 0, 4.0), (3, 128, 1, 1.0)])
+@pytest.mark.parametrize("f, s, sink, qscale", [(6, 200, 1, 1.0), (5, 333, 0, 4.0), (3, 128, 1, 1.0), (1, 50, 1, 1.0),
+                                                  (40, 3, 0, 1.0), (2, 300, 5, 0.25)])
 def test_forward_with_8bit_scores_matches_the_oracle_on_dequantised_inputs(f, s, sink, qscale):
     B, H, D, block = 1, 2, 128, 128
     N = f * s
