@@ -19,6 +19,8 @@
 // barrier): otherwise the compiler orders every LDS read after all outstanding copies.
 // 16-byte pieces are XOR-swizzled inside 256-byte LDS lines so that the 128-bit K reads and
 // the 64-bit transposing V reads are bank-conflict free.
+#include <type_traits>
+
 #include "radial_internal.h"
 #include "radial_tile.h"
 
@@ -187,7 +189,7 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_fwd_kernel(const FwdArgs a)
 
   // One stage: scores of 64 keys, online softmax, O update.  spread_lanes (all or none): also issue this
   // wave's copies of the next stage between the MFMAs of the first product.
-  auto stage_body = [&](int buf, int32_t key0, int32_t key0_next, const StageRule& vis, uint64_t spread_lanes) {
+  auto stage_body = [&](int buf, int32_t key0, int32_t key0_next, const StageRule& vis, uint64_t spread_lanes) __attribute__((always_inline)) {
     const uint32_t kdst_next = lds_base + (buf ^ 1) * 2 * T::kStageBytes + wave * T::kLoadsPerWave * 1024;
     const uint32_t vdst_next = kdst_next + T::kStageBytes;
     const __bf16* kbase_next = kp + (int64_t)key0_next * a.k.sn;  // wave-uniform
@@ -287,8 +289,10 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_fwd_kernel(const FwdArgs a)
       }
   };
 
-  for (int32_t u = 0; u < n_stage; ++u) {
-    const int buf = u & 1;
+  // Two stages per trip, so that the stage buffer of each half is a compile-time constant and the
+  // LDS addresses of its reads are immediates.
+  auto one_stage = [&](int32_t u, auto buf_c) __attribute__((always_inline)) {
+    constexpr int buf = decltype(buf_c)::value;
     // First key of stage u+1.
     int32_t key0_next = 0;
     const bool has_next = u + 1 < n_stage;
@@ -323,6 +327,10 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_fwd_kernel(const FwdArgs a)
     }
     key0 = key0_next;
     k_at = k_at_next;
+  };
+  for (int32_t u = 0; u < n_stage; u += 2) {
+    one_stage(u, std::integral_constant<int, 0>{});
+    if (u + 1 < n_stage) one_stage(u + 1, std::integral_constant<int, 1>{});
   }
 
   // ---- epilogue: O / l, LSE ----------------------------------------------------------------
