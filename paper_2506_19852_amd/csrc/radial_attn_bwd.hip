@@ -20,6 +20,8 @@
 //             here (7 products in total instead of 5), which is cheaper than pushing every
 //             listed pair's 64 KiB of dQ partial sums through memory atomics.
 // Stage tiles are copied HBM -> LDS by global_load_lds, double buffered, one stage ahead.
+#include <atomic>
+
 #include "radial_internal.h"
 #include "radial_tile.h"
 
@@ -599,11 +601,16 @@ int launch(const BwdArgs& a, hipStream_t stream) {
   const int64_t grid_q = 8LL * a.B * a.H * a.max_slice;
   if (prep_grid > 0x7fffffffLL || grid_kv > 0x7fffffffLL || grid_q > 0x7fffffffLL)
     return fail(RADIAL_ESHAPE, "problem too large for one launch");
-  static bool configured = false;  // per template instance
-  if (!configured) {
+  // The dK/dV kernel needs more dynamic LDS than the default limit.  The attribute belongs to the
+  // (device, kernel) pair; it is set once per device and template instance.  Setting it twice is
+  // harmless, so two host threads racing through here only repeat the call.
+  static std::atomic<bool> configured[kMaxDevices];
+  int dev = 0;
+  RADIAL_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices || !configured[dev].load(std::memory_order_acquire)) {
     RADIAL_HIP_TRY(hipFuncSetAttribute((const void*)radial_bwd_dkdv_kernel<D, BLK, kExact>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, T::kLdsBytes));
-    configured = true;
+    if (dev >= 0 && dev < kMaxDevices) configured[dev].store(true, std::memory_order_release);
   }
   bwd_prepare_kernel<D><<<dim3((unsigned)prep_grid), dim3(256), 0, stream>>>(a);
   if (grid_kv > 0)

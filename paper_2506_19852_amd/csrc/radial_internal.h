@@ -34,6 +34,8 @@ struct radial_mask {
 
 namespace radial {
 
+constexpr int kMaxDevices = 64;  // per-device tables of the library are this long
+
 // Records a message for radial_last_error() and returns `code`.
 int fail(int code, const char* fmt, ...);
 

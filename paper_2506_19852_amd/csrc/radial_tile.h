@@ -49,12 +49,12 @@ __device__ __forceinline__ bf16x8 as_bf16x8(uint32_t a, uint32_t b, uint32_t c, 
 // from assembly so that the compiler does not order later LDS reads after it; the caller
 // waits with wait_all_copies() and a barrier before anyone reads the destination.
 __device__ __forceinline__ void copy16_to_lds(const void* gptr, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory");
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory", "m0");
 }
 // copy16_to_lds with the address split into a wave-uniform 64-bit base (SGPRs) and a per-lane
 // 32-bit byte offset, so that walking to the next tile costs scalar arithmetic only.
 __device__ __forceinline__ void copy16_to_lds_sv(const void* base, uint32_t byte_offset, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(byte_offset), "s"(base) : "memory");
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(byte_offset), "s"(base) : "memory", "m0");
 }
 // copy16_to_lds_sv for the lanes set in `lanes` only (all or none in practice: with no lane the
 // instruction is a no-op, which lets straight-line code switch a copy off without a branch).
@@ -63,7 +63,7 @@ __device__ __forceinline__ void copy16_to_lds_sv_masked(const void* base, uint32
   lanes = ((uint64_t)__builtin_amdgcn_readfirstlane((uint32_t)(lanes >> 32)) << 32) | __builtin_amdgcn_readfirstlane((uint32_t)lanes);
   uint64_t saved;
   asm volatile("s_mov_b32 m0, %1\n\ts_and_saveexec_b64 %0, %4\n\tglobal_load_lds_dwordx4 %2, %3\n\ts_mov_b64 exec, %0"
-               : "=&s"(saved) : "s"(lds_addr), "v"(byte_offset), "s"(base), "s"(lanes) : "memory", "scc");
+               : "=&s"(saved) : "s"(lds_addr), "v"(byte_offset), "s"(base), "s"(lanes) : "memory", "scc", "m0");
 }
 // The 4-byte form of copy16_to_lds_sv_masked (256 bytes per wave).
 __device__ __forceinline__ void copy4_to_lds_sv_masked(const void* base, uint32_t byte_offset, uint32_t lds_addr, uint64_t lanes) {
@@ -71,11 +71,11 @@ __device__ __forceinline__ void copy4_to_lds_sv_masked(const void* base, uint32_
   lanes = ((uint64_t)__builtin_amdgcn_readfirstlane((uint32_t)(lanes >> 32)) << 32) | __builtin_amdgcn_readfirstlane((uint32_t)lanes);
   uint64_t saved;
   asm volatile("s_mov_b32 m0, %1\n\ts_and_saveexec_b64 %0, %4\n\tglobal_load_lds_dword %2, %3\n\ts_mov_b64 exec, %0"
-               : "=&s"(saved) : "s"(lds_addr), "v"(byte_offset), "s"(base), "s"(lanes) : "memory", "scc");
+               : "=&s"(saved) : "s"(lds_addr), "v"(byte_offset), "s"(base), "s"(lanes) : "memory", "scc", "m0");
 }
 // Same as copy16_to_lds with 4 bytes per lane (256 bytes per wave).
 __device__ __forceinline__ void copy4_to_lds(const void* gptr, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_addr), "v"(gptr) : "memory");
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_addr), "v"(gptr) : "memory", "m0");
 }
 __device__ __forceinline__ void wait_all_copies() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
