@@ -17,7 +17,8 @@
  *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream).  Attention
  *     calls are asynchronous on that stream; mask construction returns after the lists are
  *     complete on the device.
- *   - The library keeps no state between calls other than what a radial_mask owns.
+ *   - Between calls the library keeps only what a radial_mask owns, a per-device note that a
+ *     kernel attribute has been set, and the device array of radial_attn_bwd_static.
  */
 #ifndef RADIAL_H_
 #define RADIAL_H_
@@ -180,6 +181,21 @@ RADIAL_API int radial_attn_bwd(int32_t B, int32_t H, int32_t N, int32_t D, radia
                     radial_tensor v, radial_tensor out, radial_tensor dout, const float* lse,
                     radial_tensor dq, radial_tensor dk, radial_tensor dv, const radial_mask* mask,
                     float scale, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* radial_attn_bwd for callers that cannot allocate device memory or carry a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * results and errors as radial_attn_bwd without `workspace`: the per-row sums live in a device
+ * array of RADIAL_BWD_STATIC_MAX_BYTES that is part of the library's code object (each GPU the
+ * library runs on holds it until the process ends).  RADIAL_ESHAPE if
+ * radial_attn_bwd_workspace(B, H, N, D, mask) exceeds RADIAL_BWD_STATIC_MAX_BYTES, i.e. if
+ * B*H*N > 6 291 456.  Calls no hipMalloc/hipFree; the first call on a device looks up the
+ * array's address.  All calls on one GPU share the array: calls whose kernels may overlap there
+ * (different streams, or several host threads) race; order them on one stream. */
+#define RADIAL_BWD_STATIC_MAX_BYTES (24u << 20)
+RADIAL_API int radial_attn_bwd_static(int32_t B, int32_t H, int32_t N, int32_t D, radial_tensor q, radial_tensor k,
+                    radial_tensor v, radial_tensor out, radial_tensor dout, const float* lse,
+                    radial_tensor dq, radial_tensor dk, radial_tensor dv, const radial_mask* mask,
+                    float scale, void* hip_stream);
 
 /* ---- 8-bit scores (optional) -------------------------------------------------------------------
  *

@@ -22,7 +22,7 @@ EXPORTS = (
     "radial_mask_info", "radial_mask_copy_to_host", "radial_mask_copy_transpose_to_host",
     "radial_mask_free", "radial_attn_fwd", "radial_attn_bwd_workspace", "radial_attn_bwd",
     "radial_attn_fwd_trace_records", "radial_attn_fwd_trace", "radial_probe_mfma_bf16",
-    "radial_quantize_fp8", "radial_attn_fwd_fp8",
+    "radial_quantize_fp8", "radial_attn_fwd_fp8", "radial_attn_bwd_static",
 )
 
 
@@ -83,6 +83,8 @@ def load():
     lib.radial_attn_bwd_workspace.restype = c_size_t
     lib.radial_attn_bwd.argtypes = [c_int32, c_int32, c_int32, c_int32] + [radial_tensor] * 5 + [c_void_p] + \
         [radial_tensor] * 3 + [c_void_p, c_float, c_void_p, c_size_t, c_void_p]
+    lib.radial_attn_bwd_static.argtypes = [c_int32, c_int32, c_int32, c_int32] + [radial_tensor] * 5 + [c_void_p] + \
+        [radial_tensor] * 3 + [c_void_p, c_float, c_void_p]
     for name in EXPORTS:
         fn = getattr(lib, name)
         if name not in ("radial_last_error", "radial_mask_free", "radial_attn_bwd_workspace", "radial_attn_fwd_trace_records"):
@@ -282,3 +284,12 @@ def radial_attn_bwd(q, k, v, out, dout, lse, dq, dk, dv, mask: RadialMask, scale
     _check(load().radial_attn_bwd(B, H, N, D, *ts, c_void_p(lse.data_ptr()), *gs, mask.handle, c_float(scale),
                                   c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
                                   _stream_ptr(stream)))
+
+
+def radial_attn_bwd_static(q, k, v, out, dout, lse, dq, dk, dv, mask: RadialMask, scale: float, stream=None):
+    """radial_attn_bwd without a workspace: the library's own device array holds the row sums."""
+    B, H, N, D = q.shape
+    ts = [_tensor(t, nm) for t, nm in ((q, "q"), (k, "k"), (v, "v"), (out, "out"), (dout, "dout"))]
+    gs = [_tensor(t, nm) for t, nm in ((dq, "dq"), (dk, "dk"), (dv, "dv"))]
+    _check(load().radial_attn_bwd_static(B, H, N, D, *ts, c_void_p(lse.data_ptr()), *gs, mask.handle, c_float(scale),
+                                         _stream_ptr(stream)))

@@ -1,6 +1,8 @@
 // C-ABI entry points of the attention calls: argument checks, then the kernel launchers.
 #include <math.h>
 
+#include <mutex>
+
 #include "radial_internal.h"
 
 using namespace radial;
@@ -92,25 +94,16 @@ extern "C" size_t radial_attn_bwd_workspace(int32_t B, int32_t H, int32_t N, int
   return delta_bytes(B, H, N);
 }
 
-extern "C" int radial_attn_bwd(int32_t B, int32_t H, int32_t N, int32_t D, radial_tensor q, radial_tensor k,
-                               radial_tensor v, radial_tensor out, radial_tensor dout, const float* lse,
-                               radial_tensor dq, radial_tensor dk, radial_tensor dv, const radial_mask* mask,
-                               float scale, void* workspace, size_t workspace_bytes, void* hip_stream) {
-  if (int rc = check_call(B, H, N, D, mask, scale)) return rc;
-  if (!(mask->flags & RADIAL_MASK_TRANSPOSE)) return fail(RADIAL_ESHAPE, "mask was built without RADIAL_MASK_TRANSPOSE");
-  if (!lse) return fail(RADIAL_EINVAL, "lse is NULL");
-  const radial_tensor* ts[] = {&q, &k, &v, &out, &dout, &dq, &dk, &dv};
-  const char* names[] = {"q", "k", "v", "out", "dout", "dq", "dk", "dv"};
-  for (int i = 0; i < 8; ++i)
-    if (int rc = check_tensor(names[i], *ts[i], D)) return rc;
-  const size_t need = radial_attn_bwd_workspace(B, H, N, D, mask);
-  if (!workspace || ((uintptr_t)workspace & 255u)) return fail(RADIAL_ESHAPE, "workspace must be a 256-byte aligned device pointer");
-  if (workspace_bytes < need) return fail(RADIAL_ESHAPE, "workspace holds %zu bytes, %zu needed", workspace_bytes, need);
+// Checks and launch shared by the two backward entry points; `delta` is device memory for
+// B*H*N floats.
+static int bwd_call(int32_t B, int32_t H, int32_t N, int32_t D, radial_tensor q, radial_tensor k, radial_tensor v,
+                    radial_tensor out, radial_tensor dout, const float* lse, radial_tensor dq, radial_tensor dk,
+                    radial_tensor dv, const radial_mask* mask, float scale, float* delta, void* hip_stream) {
   BwdArgs a;
   a.q = arg(q); a.k = arg(k); a.v = arg(v); a.o = arg(out); a.dout = arg(dout);
   a.dq = arg(dq); a.dk = arg(dk); a.dv = arg(dv);
   a.lse = lse;
-  a.delta = (float*)workspace;
+  a.delta = delta;
   a.row_ptr = mask->d_row_ptr; a.col_idx = mask->d_col_idx;
   a.col_ptr = mask->d_col_ptr; a.row_idx = mask->d_row_idx;
   a.slice = mask->d_slice; a.max_slice = mask->max_slice;
@@ -119,6 +112,74 @@ extern "C" int radial_attn_bwd(int32_t B, int32_t H, int32_t N, int32_t D, radia
   a.scale = scale;
   a.rule = make_token_rule(mask);
   return launch_bwd(D, mask->block, a, (hipStream_t)hip_stream);
+}
+
+static int check_bwd(int32_t B, int32_t H, int32_t N, int32_t D, radial_tensor q, radial_tensor k, radial_tensor v,
+                     radial_tensor out, radial_tensor dout, const float* lse, radial_tensor dq, radial_tensor dk,
+                     radial_tensor dv, const radial_mask* mask, float scale) {
+  if (int rc = check_call(B, H, N, D, mask, scale)) return rc;
+  if (!(mask->flags & RADIAL_MASK_TRANSPOSE)) return fail(RADIAL_ESHAPE, "mask was built without RADIAL_MASK_TRANSPOSE");
+  if (!lse) return fail(RADIAL_EINVAL, "lse is NULL");
+  const radial_tensor* ts[] = {&q, &k, &v, &out, &dout, &dq, &dk, &dv};
+  const char* names[] = {"q", "k", "v", "out", "dout", "dq", "dk", "dv"};
+  for (int i = 0; i < 8; ++i)
+    if (int rc = check_tensor(names[i], *ts[i], D)) return rc;
+  return RADIAL_OK;
+}
+
+extern "C" int radial_attn_bwd(int32_t B, int32_t H, int32_t N, int32_t D, radial_tensor q, radial_tensor k,
+                               radial_tensor v, radial_tensor out, radial_tensor dout, const float* lse,
+                               radial_tensor dq, radial_tensor dk, radial_tensor dv, const radial_mask* mask,
+                               float scale, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (int rc = check_bwd(B, H, N, D, q, k, v, out, dout, lse, dq, dk, dv, mask, scale)) return rc;
+  const size_t need = radial_attn_bwd_workspace(B, H, N, D, mask);
+  if (!workspace || ((uintptr_t)workspace & 255u)) return fail(RADIAL_ESHAPE, "workspace must be a 256-byte aligned device pointer");
+  if (workspace_bytes < need) return fail(RADIAL_ESHAPE, "workspace holds %zu bytes, %zu needed", workspace_bytes, need);
+  return bwd_call(B, H, N, D, q, k, v, out, dout, lse, dq, dk, dv, mask, scale, (float*)workspace, hip_stream);
+}
+
+// ---- backward without a workspace argument --------------------------------------------------
+// The per-row sums `delta` live in a device array that is part of the library's code object:
+// every GPU the library runs on holds its own copy, at its own address, until the process ends.
+// The array's name below is only the host-side handle of that symbol; kernels get the device
+// address that hipGetSymbolAddress returns for the current device.
+static __device__ __align__(256) unsigned char scratch[RADIAL_BWD_STATIC_MAX_BYTES];
+
+namespace {
+std::mutex scratch_mutex;
+void* scratch_ptr[kMaxDevices];  // device address of `scratch`, per device; null until first use there
+
+// Device address of `scratch` on the current device (looked up once per device).
+int scratch_on_current_device(void** out) {
+  int dev = -1;
+  RADIAL_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(RADIAL_EUNSUPPORTED, "device index %d is beyond the %d the library tracks", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(scratch_mutex);
+  if (!scratch_ptr[dev]) {
+    void* p = nullptr;
+    RADIAL_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p || ((uintptr_t)p & 255u)) return fail(RADIAL_EHIP, "the library's device scratch array has no usable address");
+    scratch_ptr[dev] = p;
+  }
+  *out = scratch_ptr[dev];
+  return RADIAL_OK;
+}
+}  // namespace
+
+extern "C" int radial_attn_bwd_static(int32_t B, int32_t H, int32_t N, int32_t D, radial_tensor q, radial_tensor k,
+                                      radial_tensor v, radial_tensor out, radial_tensor dout, const float* lse,
+                                      radial_tensor dq, radial_tensor dk, radial_tensor dv, const radial_mask* mask,
+                                      float scale, void* hip_stream) {
+  if (int rc = check_bwd(B, H, N, D, q, k, v, out, dout, lse, dq, dk, dv, mask, scale)) return rc;
+  const size_t need = radial_attn_bwd_workspace(B, H, N, D, mask);
+  if (need == 0 || need > (size_t)RADIAL_BWD_STATIC_MAX_BYTES)
+    return fail(RADIAL_ESHAPE, "B*H*N = %lld rows need %zu bytes of scratch; radial_attn_bwd_static holds %zu (use radial_attn_bwd)",
+                (long long)B * H * N, need, (size_t)RADIAL_BWD_STATIC_MAX_BYTES);
+  void* delta = nullptr;
+  if (int rc = scratch_on_current_device(&delta)) return rc;
+  // Every row of delta that the kernels read is written first by the prepare kernel of this same
+  // call, so nothing has to be cleared; what an earlier call left behind is never read.
+  return bwd_call(B, H, N, D, q, k, v, out, dout, lse, dq, dk, dv, mask, scale, (float*)delta, hip_stream);
 }
 
 extern "C" int radial_quantize_fp8(int32_t B, int32_t H, int32_t N, int32_t D, radial_tensor x, int32_t block,

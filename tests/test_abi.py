@@ -16,7 +16,7 @@ def _declared():
 
 def test_header_symbols_are_exported():
     names = _declared()
-    assert len(names) == 17 and set(names) == set(binding.EXPORTS)
+    assert len(names) == 18 and set(names) == set(binding.EXPORTS)
     lib = ctypes.CDLL(binding.lib_path())
     for n in names:
         assert hasattr(lib, n), n
