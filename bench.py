@@ -21,13 +21,39 @@ if ROOT not in sys.path:
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 
-# HBM-side bytes per forward launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes in
-# profiles/ (FETCH_SIZE scaled by 2.0, WRITE_SIZE by 1.0: what the same counters read for a
-# streaming kernel of known size in the same run).  None where no pass has been recorded.
-MEASURED_TRAFFIC_BYTES = {
-    "cfg3_hunyuan720p": 2.35901e8 * 1024 * 2.0 + 7.2464e5 * 1024,
-    "cfg5_wan480p_4x_bwd": 3.84358e8 * 1024 * 2.0 + 1.28601e6 * 1024,
-}
+PROFILES = os.path.join(ROOT, "profiles")
+
+
+def traffic_from_profile(workload: str, timed_kernel_ms: float, copy_bytes: float):
+    """HBM-side bytes per forward launch from the committed rocprofv3 counter summary of this
+    workload (profiles/fwd_<workload>.txt): FETCH_SIZE and WRITE_SIZE of the radial-list launches
+    (KiB per dispatch), each scaled by what the same counter read for a streaming copy of known
+    size in the same run.  Returns (bytes or None, source): None when there is no summary or
+    when the kernel time recorded in it differs from the one timed now by more than 3 %, i.e.
+    when the counters were not taken on the kernel that is running."""
+    import re
+    path = os.path.join(PROFILES, f"fwd_{workload}.txt")
+    src = {"file": os.path.relpath(path, ROOT), "kernel_ms_at_capture": None}
+    try:
+        text = open(path).read()
+    except OSError:
+        return None, dict(src, note="no counter summary for this workload")
+    def grab(pattern):
+        m = re.search(pattern, text, flags=re.M)
+        return float(m.group(1)) if m else None
+    ms = grab(r"^radial_fwd\w*<[^>]*> radial list\s+\d+\s+([0-9.]+)")
+    fetch = grab(r"radial list\s+FETCH_SIZE\s+avg/launch ([0-9.e+]+)")
+    write = grab(r"radial list\s+WRITE_SIZE\s+avg/launch ([0-9.e+]+)")
+    cp_fetch = grab(r"copy probe[^\n]*FETCH_SIZE ([0-9.e+]+) KiB")
+    cp_write = grab(r"copy probe[^\n]*WRITE_SIZE ([0-9.e+]+) KiB")
+    src["kernel_ms_at_capture"] = ms
+    if None in (ms, fetch, write, cp_fetch, cp_write):
+        return None, dict(src, note="summary lacks a figure")
+    if abs(ms - timed_kernel_ms) > 0.03 * timed_kernel_ms:
+        return None, dict(src, note="kernel time differs from the captured one by more than 3 %")
+    known_kib = copy_bytes / 1024.0
+    src["fetch_scale"], src["write_scale"] = round(known_kib / cp_fetch, 3), round(known_kib / cp_write, 3)
+    return (fetch * known_kib / cp_fetch + write * known_kib / cp_write) * 1024.0, src
 
 
 def effective_flops(row_ptr, col_idx, n_tokens, block, D, heads):
@@ -41,24 +67,33 @@ def effective_flops(row_ptr, col_idx, n_tokens, block, D, heads):
     return 4 * D * pairs * heads
 
 
-def cpu_baseline(w, x, row_ptr, col_idx, budget_s=12.0):
+def cpu_baseline(w, x, row_ptr, col_idx, gpu_out=None, budget_s=12.0, max_blocks=None):
     """Times the CPU oracle (float64 numpy, as it stands) on query blocks of head 0 until the
-    time budget is used; reports TFLOP/s with the same flop count as the GPU metric."""
+    time budget is used; reports TFLOP/s with the same flop count as the GPU metric.  With
+    gpu_out (the forward result, [B, H, N, D]) it also reports the largest absolute and relative
+    error of the GPU result on the blocks the oracle computed."""
     import numpy as np
     from oracle import attention as oa
     q, k, v = (x[n][0, 0].float().cpu().numpy() for n in ("q", "k", "v"))
+    got = gpu_out[0, 0].float().cpu().numpy() if gpu_out is not None else None
     nb = row_ptr.size - 1
     picks = np.random.default_rng(w.seed).permutation(nb)
     done, flops, t0 = 0, 0, time.perf_counter()
+    max_abs, max_ref, max_rel = 0.0, 0.0, 0.0
     for qb in picks:
         cols = col_idx[row_ptr[qb]:row_ptr[qb + 1]]
         keys = (cols[:, None].astype(np.int64) * w.block + np.arange(w.block)[None, :]).ravel()
         keys = keys[keys < w.N]
         rows = np.arange(qb * w.block, min(w.N, (qb + 1) * w.block))
-        oa.attention_rows_keyset(q[rows], k, v, keys, w.scale)
+        ref = oa.attention_rows_keyset(q[rows], k, v, keys, w.scale)[0]
         flops += 4 * w.D * rows.size * keys.size
         done += 1
-        if time.perf_counter() - t0 > budget_s:
+        if got is not None:
+            err = np.abs(got[rows] - ref)
+            max_abs = max(max_abs, float(err.max()))
+            max_ref = max(max_ref, float(np.abs(ref).max()))
+            max_rel = max(max_rel, float((err / (1e-2 + 1e-2 * np.abs(ref))).max()))
+        if time.perf_counter() - t0 > budget_s or (max_blocks is not None and done >= max_blocks):
             break
     dt = time.perf_counter() - t0
     try:
@@ -67,9 +102,14 @@ def cpu_baseline(w, x, row_ptr, col_idx, budget_s=12.0):
     except Exception:
         cores = os.cpu_count() or 1
     total = effective_flops(row_ptr, col_idx, w.N, w.block, w.D, w.B * w.H)
-    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"{done} of {nb} query blocks of head 0 ({w.name}), float64 numpy, {dt:.1f} s",
-            "sampled_fraction_of_flops": flops / total, "extrapolated_full_forward_s": dt * total / flops}
+    res = {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+           "sample": f"{done} of {nb} query blocks of head 0 ({w.name}), float64 numpy, {dt:.1f} s",
+           "sampled_fraction_of_flops": flops / total, "extrapolated_full_forward_s": dt * total / flops}
+    if got is not None:
+        # err / (1e-2 + 1e-2 |ref|) <= 1 is the tolerance of the parity tests (1e-2 absolute + 1e-2 relative)
+        res.update({"gpu_max_abs_err": max_abs, "gpu_max_abs_err_over_max_ref": max_abs / max_ref if max_ref else None,
+                    "gpu_max_err_over_tolerance": max_rel * 1.0, "max_abs_ref": max_ref})
+    return res
 
 
 def load_balance(trace):
@@ -92,6 +132,85 @@ def load_balance(trace):
             "cu_busy_frac_min_mean_max": [round(float(occ.min()), 3), round(float(occ.mean()), 3), round(float(occ.max()), 3)],
             "xcd_finish_frac_min_max": [round(float(last.min() / span), 3), round(float(last.max() / span), 3)],
             "xcd_is_workgroup_id_mod_8": round(float(np.mean(xcc == (np.nonzero(used)[0] & 7))), 4)}
+
+
+def oracle_dq_error(w, x, grads, row_ptr, col_idx, qb):
+    """Largest error of the GPU's dQ on query block qb of head 0 against the float64 oracle, as a
+    multiple of the parity tolerance (1e-2 + 1e-2 |ref|).  Part of the CPU-baseline leg."""
+    import numpy as np
+    from oracle import attention as oa
+    q, k, v, do = (x[n][0, 0].float().cpu().numpy() for n in ("q", "k", "v", "do"))
+    cols = col_idx[row_ptr[qb]:row_ptr[qb + 1]]
+    keys = (cols[:, None].astype(np.int64) * w.block + np.arange(w.block)[None, :]).ravel()
+    keys = keys[keys < w.N]
+    rows = np.arange(qb * w.block, min(w.N, (qb + 1) * w.block))
+    ref = oa.attention_bwd_keyset(q[rows], k, v, keys, w.scale, do[rows])[0]
+    err = np.abs(grads[0][0, 0, rows[0]:rows[-1] + 1].float().cpu().numpy() - ref)
+    return {"dq_max_abs_err": float(err.max()), "dq_max_abs_ref": float(np.abs(ref).max()),
+            "dq_max_err_over_tolerance": float((err / (1e-2 + 1e-2 * np.abs(ref))).max())}
+
+
+def secondary_config(name, args, with_oracle):
+    """One line of the `secondary` array: forward (and backward) kernel times of another
+    workload, timed with events on the launch stream over a few launches, the same forward on
+    the all-ones list, and -- inside the CPU-baseline leg -- the error of the GPU result on a
+    sampled query block against the oracle."""
+    import numpy as np
+    import torch
+    from paper_2506_19852_amd import binding as rb
+    from paper_2506_19852_amd import workloads as wl
+    w = wl.WORKLOADS[name]
+    dev = "cuda:0"
+    x = wl.make_inputs(w, dev)
+    out = torch.empty_like(x["q"])
+    lse = torch.empty((w.B, w.H, w.N), dtype=torch.float32, device=dev)
+    m = rb.radial_mask_build(w.frames, w.tokens_per_frame, w.block, 1, rb.RADIAL_MASK_TRANSPOSE if w.backward else 0)
+    row_ptr, col_idx = rb.radial_mask_copy_to_host(m)
+    flops = effective_flops(row_ptr, col_idx, w.N, w.block, w.D, w.B * w.H)
+
+    def timed(fn, launches):
+        fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(launches):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        return float(np.mean(ts))
+
+    n = args.secondary_launches
+    fwd_ms = timed(lambda: rb.radial_attn_fwd(x["q"], x["k"], x["v"], out, lse, m, w.scale), n)
+    line = {"workload": w.name, "pass": "fwd+bwd" if w.backward else "fwd", "B": w.B, "H": w.H, "N": w.N, "D": w.D,
+            "listed_block_pairs": int(row_ptr[-1]), "launches": n, "fwd_kernel_ms": round(fwd_ms, 3),
+            "fwd_tflops": round(flops / fwd_ms / 1e9, 1), "fwd_frac": round(flops / fwd_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)}
+    grads = None
+    if w.backward:
+        grads = [torch.empty_like(x["q"]) for _ in range(3)]
+        ws = torch.empty(rb.radial_attn_bwd_workspace(w.B, w.H, w.N, w.D, m), dtype=torch.uint8, device=dev)
+        bwd_ms = timed(lambda: rb.radial_attn_bwd(x["q"], x["k"], x["v"], out, x["do"], lse, *grads, m, w.scale, ws), n)
+        # the gradient needs 5 products per listed pair against the forward's 2
+        line.update({"bwd_kernels_ms": round(bwd_ms, 3), "bwd_tflops": round(2.5 * flops / bwd_ms / 1e9, 1),
+                     "bwd_frac": round(2.5 * flops / bwd_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4),
+                     "fwd_bwd_tflops": round(3.5 * flops / (fwd_ms + bwd_ms) / 1e9, 1)})
+    if with_oracle:
+        base = cpu_baseline(w, x, row_ptr, col_idx, gpu_out=out, budget_s=4.0, max_blocks=2)
+        line["oracle_check"] = {k2: base[k2] for k2 in ("sample", "gpu_max_abs_err", "max_abs_ref", "gpu_max_err_over_tolerance")}
+        if w.backward:
+            line["oracle_check"].update(oracle_dq_error(w, x, grads, row_ptr, col_idx, int(np.argmax(np.diff(row_ptr)))))
+    m.free()
+    dense = rb.radial_mask_build_dense(w.N, w.block)
+    dptr, didx = rb.radial_mask_copy_to_host(dense)
+    dense_flops = effective_flops(dptr, didx, w.N, w.block, w.D, w.B * w.H)
+    dense_ms = timed(lambda: rb.radial_attn_fwd(x["q"], x["k"], x["v"], out, None, dense, w.scale), 1)
+    dense.free()
+    line.update({"dense_fwd_kernel_ms": round(dense_ms, 3), "dense_tflops": round(dense_flops / dense_ms / 1e9, 1),
+                 "speedup_vs_dense": round(dense_ms / fwd_ms, 3), "block_ratio_dense_over_radial": round(dense_flops / flops, 3)})
+    del x, out, lse, grads
+    torch.cuda.empty_cache()
+    return line
 
 
 def complexity_curve(frames_list, heads, args):
@@ -178,6 +297,13 @@ def main():
     ap.add_argument("--curve-frames", default=None, metavar="F1,F2,...",
                     help="instead of the benchmark line: forward time vs video length at the 720p geometry (s = 3600)")
     ap.add_argument("--curve-heads", type=int, default=2)
+    ap.add_argument("--secondary", default="cfg2_wan480p,cfg4_hunyuan720p_4x,cfg5_wan480p_4x_bwd", metavar="W1,W2,...",
+                    help="other workloads reported in the line's `secondary` array (kernel times only; 'none' to skip)")
+    ap.add_argument("--secondary-launches", type=int, default=2)
+    ap.add_argument("--cache-probe", action="store_true",
+                    help="also run a streaming read of 2 GiB and 16 re-reads of a 64 MiB tensor (torch.neg), so that a "
+                         "rocprofv3 --pmc TCC_EA0_RDREQ_sum TCC_EA0_RDREQ_LEVEL_sum run can compare the read latency seen "
+                         "by the attention kernel's L2 misses with HBM reads and with reads the last-level cache serves")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -259,6 +385,17 @@ def main():
     if args.copy_probe:
         torch.neg(x["q"], out=out)     # one streaming kernel: reads and writes q.numel()*2 bytes
         torch.cuda.synchronize()
+    if args.cache_probe:
+        big = torch.zeros(1 << 30, dtype=torch.bfloat16, device=dev)      # 2 GiB: larger than every cache
+        torch.neg(big, out=big)
+        torch.cuda.synchronize()
+        del big
+        small = torch.zeros(32 << 20, dtype=torch.bfloat16, device=dev)   # 64 MiB: fits the last-level cache, not the L2s
+        dst = torch.empty_like(small)
+        for _ in range(16):
+            torch.neg(small, out=dst)
+        torch.cuda.synchronize()
+        del small, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -309,7 +446,7 @@ def main():
         torch.cuda.synchronize()
         balance = load_balance(trace.cpu().numpy())
         del trace
-    m.free()
+    keep_mask = m
 
     # the matrix pipes alone, at the clock the chip sustains: dependent MFMAs on registers
     probe_iters = 20000
@@ -322,6 +459,9 @@ def main():
     probe_tflops = probe_flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
 
     achieved = fwd_flops / (kernel_ms * 1e-3) / 1e12
+    traffic, traffic_source = None, None
+    if width_num == width_den and not args.token_exact and args.pattern == "radial" and quant is None:
+        traffic, traffic_source = traffic_from_profile(w.name, kernel_ms, float(x["q"].numel() * 2))
     result = {
         "metric": "effective TFLOP/s on computed blocks + speedup vs dense attn at same N, 1 GPU",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -343,7 +483,8 @@ def main():
         "speedup_vs_dense": round(dense_ms / kernel_ms, 3),
         "block_ratio_dense_over_radial": round(dense_flops / fwd_flops, 3),
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "frac_of_mfma_probe": round(achieved / probe_tflops, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if (width_num == width_den and not args.token_exact and args.pattern == "radial") else None,
+                     "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "frac_of_mfma_probe": round(achieved / probe_tflops, 4),
+                     "traffic": traffic, "traffic_source": traffic_source,
                      "kernel": "radial_fwd_kernel", "flops_per_launch": fwd_flops},
     }
     if quant is not None:
@@ -352,7 +493,16 @@ def main():
         result["roofline"]["traffic"] = None
         result["roofline"]["note"] = "half of the flops run on the 8-bit matrix instruction; peak and frac are still the bf16 figures"
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, x, row_ptr, col_idx)
+        forward(keep_mask, None)                       # the result the oracle's sample is compared with
+        torch.cuda.synchronize()
+        result["cpu_baseline"] = cpu_baseline(w, x, row_ptr, col_idx, gpu_out=out)
+    keep_mask.free()
+    names = [] if args.secondary in ("", "none") or quant is not None or args.token_exact or args.pattern != "radial" \
+        or width_num != width_den else [t for t in args.secondary.split(",") if t != w.name]
+    if names:
+        del x, out, lse, grads
+        torch.cuda.empty_cache()
+        result["secondary"] = [secondary_config(nm, args, not args.no_cpu_baseline) for nm in names]
     print(json.dumps(result))
 
 
