@@ -10,7 +10,7 @@ from oracle import mask as om
 from paper_2506_19852_amd import binding as rb
 from paper_2506_19852_amd import workloads as wl
 
-from util import assert_close, sample_qblocks
+from util import assert_close, backward_rounding_bounds, sample_qblocks
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -156,9 +156,10 @@ def test_backward_small(f, s, block, D, B, H, sink, qscale):
     for b in range(B):
         for h in range(H):
             qh, kh, vh, gh = (t[b, h].float().cpu().numpy() for t in (q, k, v, do))
-            ref = oa.attention_bwd_rows(qh, kh, vh, vis, scale, gh)[:3]
-            for got, want, nm in zip((dq, dk, dv), ref, ("dQ", "dK", "dV")):
-                assert_close(got[b, h].float().cpu().numpy(), want, f"exact b{b} h{h} {nm}", scaled_atol=qscale != 1.0)
+            ref, bounds = backward_rounding_bounds(qh, kh, vh, vis, scale, gh)
+            for got, want, bound, nm in zip((dq, dk, dv), ref, bounds, ("dQ", "dK", "dV")):
+                assert_close(got[b, h].float().cpu().numpy(), want, f"exact b{b} h{h} {nm}",
+                             extra_atol=2.0 * bound if qscale != 1.0 else None)
     mask.free()
 
 
@@ -190,12 +191,16 @@ def test_workload_backward(capsys):
     for qb in sorted({0, nb - 1, s // block, *rng.integers(0, nb, 5).tolist()}):
         rows, _, ref_dq, _, _ = block_grads(qb)
         assert_close(dq[0, head, rows[0]:rows[-1] + 1].float().cpu().numpy(), ref_dq, f"exact cfg5 dQ qb{qb}")
-    col_ptr, row_idx = rb.radial_mask_copy_transpose_to_host(mask)
-    kb = int(np.argmin(np.diff(col_ptr)[nb // 4: 3 * nb // 4])) + nb // 4    # the shortest column of the middle half
+    # which query blocks list key block kb comes from the oracle's own block mask (a query block the
+    # library's transposed list had dropped would otherwise be missing from both sides)
+    bitmap, _ = obuild.mask_scan(f, s, block, 1)
+    col_len = bitmap.sum(axis=0)
+    kb = int(np.argmin(col_len[nb // 4: 3 * nb // 4])) + nb // 4              # the shortest column of the middle half
     kcols = np.arange(kb * block, min(w.N, (kb + 1) * block))
     ref_dk = np.zeros((kcols.size, w.D))
     ref_dv = np.zeros((kcols.size, w.D))
-    listers = row_idx[col_ptr[kb]:col_ptr[kb + 1]]
+    listers = np.flatnonzero(bitmap[:, kb])
+    assert listers.size > 128                                               # the kernel reloads its list chunk
     for n_done, qb in enumerate(listers):
         _, keys, _, g_k, g_v = block_grads(int(qb))
         pos = np.searchsorted(keys, kcols)
