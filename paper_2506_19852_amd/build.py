@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libradial.so")
-SOURCES = ["radial_mask.hip", "radial_api.hip", "radial_attn_fwd.hip", "radial_attn_fwd_fp8.hip", "radial_attn_bwd.hip"]
+SOURCES = ["radial_mask.hip", "radial_api.hip", "radial_attn_fwd.hip", "radial_attn_fwd_fp8.hip", "radial_attn_bwd.hip", "radial_diag.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",

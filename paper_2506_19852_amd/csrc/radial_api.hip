@@ -35,52 +35,33 @@ TensorArg arg(const radial_tensor& t) { return TensorArg{t.ptr, t.stride_b, t.st
 
 }  // namespace
 
-static int fwd_call(int32_t B, int32_t H, int32_t N, int32_t D, radial_tensor q, radial_tensor k, radial_tensor v,
-                    radial_tensor out, float* lse, const radial_mask* mask, float scale, void* hip_stream,
-                    uint64_t* trace, int64_t trace_records) {
+// Argument checks of a forward call; fills *a (without trace records).
+int radial::make_fwd_args(int32_t B, int32_t H, int32_t N, int32_t D, radial_tensor q, radial_tensor k, radial_tensor v,
+                          radial_tensor out, float* lse, const radial_mask* mask, float scale, FwdArgs* a) {
   if (int rc = check_call(B, H, N, D, mask, scale)) return rc;
   if (int rc = check_tensor("q", q, D)) return rc;
   if (int rc = check_tensor("k", k, D)) return rc;
   if (int rc = check_tensor("v", v, D)) return rc;
   if (int rc = check_tensor("out", out, D)) return rc;
-  FwdArgs a;
-  a.q = arg(q); a.k = arg(k); a.v = arg(v); a.o = arg(out);
-  a.lse = lse;
-  a.row_ptr = mask->d_row_ptr;
-  a.col_idx = mask->d_col_idx;
-  a.slice = mask->d_slice;
-  a.max_slice = mask->max_slice;
-  a.B = B; a.H = H; a.N = N; a.n_blocks = mask->n_blocks;
-  a.scale = scale;
-  a.rule = make_token_rule(mask);
-  a.wg_trace = trace;
-  if (trace && trace_records < fwd_grid(a))
-    return fail(RADIAL_ESHAPE, "trace holds %lld records, %lld needed", (long long)trace_records, (long long)fwd_grid(a));
-  return launch_fwd(D, mask->block, a, (hipStream_t)hip_stream);
+  a->q = arg(q); a->k = arg(k); a->v = arg(v); a->o = arg(out);
+  a->lse = lse;
+  a->row_ptr = mask->d_row_ptr;
+  a->col_idx = mask->d_col_idx;
+  a->slice = mask->d_slice;
+  a->max_slice = mask->max_slice;
+  a->B = B; a->H = H; a->N = N; a->n_blocks = mask->n_blocks;
+  a->scale = scale;
+  a->rule = make_token_rule(mask);
+  a->wg_trace = nullptr;
+  return RADIAL_OK;
 }
 
 extern "C" int radial_attn_fwd(int32_t B, int32_t H, int32_t N, int32_t D, radial_tensor q, radial_tensor k,
                                radial_tensor v, radial_tensor out, float* lse, const radial_mask* mask, float scale,
                                void* hip_stream) {
-  return fwd_call(B, H, N, D, q, k, v, out, lse, mask, scale, hip_stream, nullptr, 0);
-}
-
-extern "C" int64_t radial_attn_fwd_trace_records(int32_t B, int32_t H, const radial_mask* mask) {
-  if (!mask || B < 1 || H < 1) return 0;
-  return 8LL * B * H * mask->max_slice;
-}
-
-extern "C" int radial_attn_fwd_trace(int32_t B, int32_t H, int32_t N, int32_t D, radial_tensor q, radial_tensor k,
-                                     radial_tensor v, radial_tensor out, float* lse, const radial_mask* mask,
-                                     float scale, void* hip_stream, uint64_t* trace, int64_t trace_records) {
-  if (!trace) return fail(RADIAL_EINVAL, "trace is NULL");
-  return fwd_call(B, H, N, D, q, k, v, out, lse, mask, scale, hip_stream, trace, trace_records);
-}
-
-extern "C" int radial_probe_mfma_bf16(int64_t iterations, void* hip_stream, double* flops) {
-  if (iterations < 4 || iterations > (1LL << 20) || (iterations & 3))
-    return fail(RADIAL_EINVAL, "iterations must be a multiple of 4 in [4, 2^20]");
-  return launch_mfma_probe(iterations, (hipStream_t)hip_stream, flops);
+  FwdArgs a;
+  if (int rc = make_fwd_args(B, H, N, D, q, k, v, out, lse, mask, scale, &a)) return rc;
+  return launch_fwd(D, mask->block, a, (hipStream_t)hip_stream);
 }
 
 // Workspace layout: delta [B*H*N] fp32.

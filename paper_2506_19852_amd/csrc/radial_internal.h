@@ -14,6 +14,10 @@ struct radial_mask {
   int64_t nnz = 0;
   uint32_t flags = 0;
   int device = 0;
+  // owners of the device storage; the pointers below are views into them
+  int32_t* d_meta = nullptr;     // totals and launch partitions
+  int32_t* d_ptrs = nullptr;     // row_ptr (+ col_ptr)
+  int32_t* d_idx = nullptr;      // col_idx (+ row_idx)
   int32_t* d_row_ptr = nullptr;  // [n_blocks + 1]
   int32_t* d_col_idx = nullptr;  // [nnz]
   int32_t* d_col_ptr = nullptr;  // [n_blocks + 1]  (transpose; only with RADIAL_MASK_TRANSPOSE)
@@ -92,6 +96,9 @@ struct FwdArgs {
 };
 
 int launch_fwd(int D, int block, const FwdArgs& a, hipStream_t stream);
+// Argument checks of a forward call (as radial_attn_fwd documents them); fills *a, wg_trace = null.
+int make_fwd_args(int32_t B, int32_t H, int32_t N, int32_t D, radial_tensor q, radial_tensor k, radial_tensor v,
+                  radial_tensor out, float* lse, const radial_mask* mask, float scale, FwdArgs* a);
 // Workgroups one forward launch of this shape starts (the number of trace records).
 int64_t fwd_grid(const FwdArgs& a);
 // Launches a kernel that only issues dependent bf16 MFMAs from registers; *flops_out (host)

@@ -263,35 +263,58 @@ int check_common(int64_t n_tokens, int32_t block, uint32_t flags) {
   return RADIAL_OK;
 }
 
-// Shared tail of the three constructors: transposed lists (optional) and launch orders.
+// Device storage of a mask is three allocations: `meta` (two 64-bit totals and the two launch
+// partitions), `ptrs` (row_ptr and, with the transposed lists, col_ptr) and `idx` (col_idx and
+// row_idx).  The views d_row_ptr, d_col_ptr, ... point into them at 256-byte aligned offsets.
+constexpr int kMetaInts = 32;  // [0..1] total of rows, [2..3] total of columns, [8..16] slice, [20..28] slice_t
+inline int64_t aligned_ints(int64_t n) { return (n + 63) & ~(int64_t)63; }
+
+int alloc_meta_and_ptrs(radial_mask* m) {
+  const int64_t np = aligned_ints((int64_t)m->n_blocks + 1);
+  RADIAL_HIP_TRY(hipMalloc(&m->d_meta, sizeof(int32_t) * kMetaInts));
+  RADIAL_HIP_TRY(hipMalloc(&m->d_ptrs, sizeof(int32_t) * np * ((m->flags & RADIAL_MASK_TRANSPOSE) ? 2 : 1)));
+  m->d_row_ptr = m->d_ptrs;
+  m->d_slice = m->d_meta + 8;
+  if (m->flags & RADIAL_MASK_TRANSPOSE) {
+    m->d_col_ptr = m->d_ptrs + np;
+    m->d_slice_t = m->d_meta + 20;
+  }
+  return RADIAL_OK;
+}
+
+// Needs m->nnz.
+int alloc_idx(radial_mask* m) {
+  const int64_t ni = aligned_ints(m->nnz > 0 ? m->nnz : 1);
+  RADIAL_HIP_TRY(hipMalloc(&m->d_idx, sizeof(int32_t) * ni * ((m->flags & RADIAL_MASK_TRANSPOSE) ? 2 : 1)));
+  m->d_col_idx = m->d_idx;
+  if (m->flags & RADIAL_MASK_TRANSPOSE) m->d_row_idx = m->d_idx + ni;
+  return RADIAL_OK;
+}
+
+// Shared tail of the constructors: transposed lists (optional) and launch partitions, then the one
+// wait of the call for everything queued on the stream (the partitions come back to the host).
 int finish_mask(radial_mask* m, hipStream_t st) {
   const int32_t nb = m->n_blocks;
-  int32_t h_slice[9];
-  RADIAL_HIP_TRY(hipMalloc(&m->d_slice, sizeof(int32_t) * 9));
+  int32_t h_meta[kMetaInts];
   slice_kernel<<<1, 64, 0, st>>>(m->d_row_ptr, nb, m->d_slice);
-  RADIAL_HIP_TRY(hipGetLastError());
-  RADIAL_HIP_TRY(hipMemcpyAsync(h_slice, m->d_slice, sizeof h_slice, hipMemcpyDeviceToHost, st));
-  RADIAL_HIP_TRY(hipStreamSynchronize(st));
-  for (int k = 0; k < 8; ++k) m->max_slice = h_slice[k + 1] - h_slice[k] > m->max_slice ? h_slice[k + 1] - h_slice[k] : m->max_slice;
   if (m->flags & RADIAL_MASK_TRANSPOSE) {
-    long long* d_total = nullptr;
-    RADIAL_HIP_TRY(hipMalloc(&m->d_col_ptr, sizeof(int32_t) * (nb + 1)));
-    RADIAL_HIP_TRY(hipMalloc(&m->d_row_idx, sizeof(int32_t) * (m->nnz > 0 ? m->nnz : 1)));
-    RADIAL_HIP_TRY(hipMalloc(&m->d_slice_t, sizeof(int32_t) * 9));
-    RADIAL_HIP_TRY(hipMalloc(&d_total, sizeof(long long)));
     transpose_count_kernel<<<nb, kThreads, 0, st>>>(m->d_row_ptr, m->d_col_idx, nb, m->d_col_ptr);
-    scan_kernel<<<1, kThreads, 0, st>>>(m->d_col_ptr, nb, d_total);
+    scan_kernel<<<1, kThreads, 0, st>>>(m->d_col_ptr, nb, (long long*)(m->d_meta + 2));
     transpose_fill_kernel<<<nb, kThreads, 0, st>>>(m->d_row_ptr, m->d_col_idx, nb, m->d_col_ptr, m->d_row_idx);
     slice_kernel<<<1, 64, 0, st>>>(m->d_col_ptr, nb, m->d_slice_t);
-    hipError_t e = hipGetLastError();
-    if (e == hipSuccess) e = hipMemcpyAsync(h_slice, m->d_slice_t, sizeof h_slice, hipMemcpyDeviceToHost, st);
-    if (e == hipSuccess) e = hipStreamSynchronize(st);
-    (void)hipFree(d_total);
-    if (e != hipSuccess) return fail(RADIAL_EHIP, "transpose kernels failed: %s", hipGetErrorString(e));
-    for (int k = 0; k < 8; ++k)
-      m->max_slice_t = h_slice[k + 1] - h_slice[k] > m->max_slice_t ? h_slice[k + 1] - h_slice[k] : m->max_slice_t;
   }
-  RADIAL_HIP_TRY(hipStreamSynchronize(st));
+  hipError_t e = hipGetLastError();
+  if (e == hipSuccess) e = hipMemcpyAsync(h_meta, m->d_meta, sizeof h_meta, hipMemcpyDeviceToHost, st);
+  if (e == hipSuccess) e = hipStreamSynchronize(st);
+  if (e != hipSuccess) return fail(RADIAL_EHIP, "mask kernels failed: %s", hipGetErrorString(e));
+  for (int k = 0; k < 8; ++k) {
+    const int32_t len = h_meta[8 + k + 1] - h_meta[8 + k];
+    m->max_slice = len > m->max_slice ? len : m->max_slice;
+    if (m->flags & RADIAL_MASK_TRANSPOSE) {
+      const int32_t len_t = h_meta[20 + k + 1] - h_meta[20 + k];
+      m->max_slice_t = len_t > m->max_slice_t ? len_t : m->max_slice_t;
+    }
+  }
   return RADIAL_OK;
 }
 
@@ -304,12 +327,9 @@ extern "C" const char* radial_last_error(void) { return radial::g_err; }
 
 extern "C" void radial_mask_free(radial_mask* m) {
   if (!m) return;
-  (void)hipFree(m->d_row_ptr);
-  (void)hipFree(m->d_col_idx);
-  (void)hipFree(m->d_col_ptr);
-  (void)hipFree(m->d_row_idx);
-  (void)hipFree(m->d_slice);
-  (void)hipFree(m->d_slice_t);
+  (void)hipFree(m->d_meta);
+  (void)hipFree(m->d_ptrs);
+  (void)hipFree(m->d_idx);
   (void)hipFree(m->d_half_width);
   delete m;
 }
@@ -340,20 +360,17 @@ static int build_radial(radial_mask* m, const radial_mask_params* p, hipStream_t
   const MaskGeom g{p->frames, p->tokens_per_frame, p->block, p->sink_frames, m->n_tokens, nb,
                    (int32_t)(s_num / p->width_den), p->width_den, s_num, m->d_half_width,
                    (int32_t)((int64_t)p->frames * p->tokens_per_frame)};
-  long long* d_total = nullptr;
   long long total = 0;
-  RADIAL_HIP_TRY(hipMalloc(&m->d_row_ptr, sizeof(int32_t) * (nb + 1)));
-  RADIAL_HIP_TRY(hipMalloc(&d_total, sizeof(long long)));
+  if (int rc = alloc_meta_and_ptrs(m)) return rc;
   mask_count_kernel<<<nb, kThreads, nwords * sizeof(uint32_t), st>>>(g, nwords, m->d_row_ptr);
-  scan_kernel<<<1, kThreads, 0, st>>>(m->d_row_ptr, nb, d_total);
+  scan_kernel<<<1, kThreads, 0, st>>>(m->d_row_ptr, nb, (long long*)m->d_meta);
   hipError_t e = hipGetLastError();
-  if (e == hipSuccess) e = hipMemcpyAsync(&total, d_total, sizeof total, hipMemcpyDeviceToHost, st);
-  if (e == hipSuccess) e = hipStreamSynchronize(st);
-  (void)hipFree(d_total);
+  if (e == hipSuccess) e = hipMemcpyAsync(&total, m->d_meta, sizeof total, hipMemcpyDeviceToHost, st);
+  if (e == hipSuccess) e = hipStreamSynchronize(st);   // the list storage is sized by the count
   if (e != hipSuccess) return fail(RADIAL_EHIP, "mask count failed: %s", hipGetErrorString(e));
   if (total > 0x7fffffffLL) return fail(RADIAL_EUNSUPPORTED, "%lld listed block pairs do not fit int32", total);
   m->nnz = total;
-  RADIAL_HIP_TRY(hipMalloc(&m->d_col_idx, sizeof(int32_t) * (total > 0 ? total : 1)));
+  if (int rc = alloc_idx(m)) return rc;
   mask_fill_kernel<<<nb, kThreads, nwords * sizeof(uint32_t), st>>>(g, nwords, m->d_row_ptr, m->d_col_idx);
   RADIAL_HIP_TRY(hipGetLastError());
   return finish_mask(m, st);
@@ -405,10 +422,9 @@ extern "C" int radial_mask_build_banded(int32_t frames, int32_t tokens_per_frame
   const hipStream_t st = (hipStream_t)hip_stream;
   int rc = RADIAL_OK;
   if (hipMalloc(&m->d_half_width, sizeof(int32_t) * table.size()) != hipSuccess ||
-      hipMemcpyAsync(m->d_half_width, table.data(), sizeof(int32_t) * table.size(), hipMemcpyHostToDevice, st) != hipSuccess ||
-      hipStreamSynchronize(st) != hipSuccess)
+      hipMemcpyAsync(m->d_half_width, table.data(), sizeof(int32_t) * table.size(), hipMemcpyHostToDevice, st) != hipSuccess)
     rc = fail(RADIAL_EHIP, "copying the half-width table failed");
-  if (!rc) {
+  if (!rc) {  // `table` stays alive until build_radial has waited for the stream
     const radial_mask_params p{frames, tokens_per_frame, block, sink_frames, flags, 1, 1, 0};
     rc = build_radial(m, &p, st);
   }
@@ -424,8 +440,8 @@ static int build_dense(radial_mask* m, hipStream_t st) {
   const int64_t nb = m->n_blocks;
   if (nb * nb > 0x7fffffffLL) return fail(RADIAL_EUNSUPPORTED, "%lld block pairs do not fit int32", (long long)(nb * nb));
   m->nnz = nb * nb;
-  RADIAL_HIP_TRY(hipMalloc(&m->d_row_ptr, sizeof(int32_t) * (nb + 1)));
-  RADIAL_HIP_TRY(hipMalloc(&m->d_col_idx, sizeof(int32_t) * m->nnz));
+  if (int rc = alloc_meta_and_ptrs(m)) return rc;
+  if (int rc = alloc_idx(m)) return rc;
   dense_fill_kernel<<<1024, kThreads, 0, st>>>((int32_t)nb, m->d_row_ptr, m->d_col_idx);
   RADIAL_HIP_TRY(hipGetLastError());
   return finish_mask(m, st);
@@ -456,12 +472,12 @@ static int build_from_csr(radial_mask* m, const int32_t* row_ptr, const int32_t*
     }
   }
   m->nnz = row_ptr[nb];
-  RADIAL_HIP_TRY(hipMalloc(&m->d_row_ptr, sizeof(int32_t) * (nb + 1)));
-  RADIAL_HIP_TRY(hipMalloc(&m->d_col_idx, sizeof(int32_t) * (m->nnz > 0 ? m->nnz : 1)));
+  if (int rc = alloc_meta_and_ptrs(m)) return rc;
+  if (int rc = alloc_idx(m)) return rc;
+  // the caller's arrays are read until finish_mask has waited for the stream
   RADIAL_HIP_TRY(hipMemcpyAsync(m->d_row_ptr, row_ptr, sizeof(int32_t) * (nb + 1), hipMemcpyHostToDevice, st));
   if (m->nnz > 0)
     RADIAL_HIP_TRY(hipMemcpyAsync(m->d_col_idx, col_idx, sizeof(int32_t) * m->nnz, hipMemcpyHostToDevice, st));
-  RADIAL_HIP_TRY(hipStreamSynchronize(st));
   return finish_mask(m, st);
 }
 

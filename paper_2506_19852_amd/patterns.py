@@ -5,6 +5,11 @@ A banded mask lets query token (i, k) attend key token (j, l) iff j is a sink fr
 |k - l| <= half_width[|i - j|]; -1 hides the frame pair.  The paper describes these masks in a
 sentence each, so every function states the reading it takes; callers with another reading
 pass their own table.
+
+These four functions are caller-side examples, not part of the library: the library's rule is
+the table lookup above and nothing else (`bench.py --pattern` uses them to pick example widths).
+The tests check the library against the oracle's own definitions of these masks with tables the
+test passes in, never against this file.
 """
 from __future__ import annotations
 

@@ -9,7 +9,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _declared():
-    text = open(os.path.join(ROOT, "include", "radial.h")).read()
+    text = "".join(open(os.path.join(ROOT, "include", h)).read() for h in ("radial.h", "radial_diag.h"))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"RADIAL_API\s+[\w\s\*]+?\b(radial_\w+)\s*\(", text)))
 

@@ -99,14 +99,3 @@ def test_block_bitmap_brute_force():
         want[q // block, c // block] = True
     got = op.block_bitmap(lambda rows: op.banded_mask_rows(f, s, 1, hw, rows), n, block)
     assert np.array_equal(got, want)
-
-
-def test_library_side_tables_take_the_same_readings():
-    # paper_2506_19852_amd/patterns.py is written independently of oracle/patterns.py
-    from paper_2506_19852_amd import patterns as pp
-    for f, s in ((33, 3600), (12, 200), (5, 7), (81, 1560)):
-        assert pp.spatial_head(f, s, 2) == op.half_widths_spatial(f, s, 2)
-        assert pp.temporal_head(f, s, 40) == op.half_widths_temporal(f, s, 40)
-        assert pp.temporal_head(f, s, 10 ** 6) == op.half_widths_temporal(f, s, 10 ** 6)
-        assert pp.sliding_window(f, s, 1, 60) == op.half_widths_sliding(f, s, 1, 60)
-        assert pp.harmonic_decay(f, s) == op.half_widths_harmonic(f, s)
