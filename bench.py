@@ -32,7 +32,8 @@ def traffic_from_profile(workload: str, timed_kernel_ms: float, copy_bytes: floa
     when the kernel time recorded in it differs from the one timed now by more than 3 %, i.e.
     when the counters were not taken on the kernel that is running."""
     import re
-    path = os.path.join(PROFILES, f"fwd_{workload}.txt")
+    name = {"cfg5_wan480p_4x_bwd": "fwd_bwd_cfg5_wan480p_4x.txt"}.get(workload, f"fwd_{workload}.txt")
+    path = os.path.join(PROFILES, name)
     src = {"file": os.path.relpath(path, ROOT), "kernel_ms_at_capture": None}
     try:
         text = open(path).read()
