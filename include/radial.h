@@ -212,13 +212,14 @@ RADIAL_API int radial_attn_bwd_static(int32_t B, int32_t H, int32_t N, int32_t D
  *
  * radial_attn_fwd_fp8 is radial_attn_fwd (Eq. 2 on the listed blocks, listed blocks dense) with
  * the scores computed from such codes: S = (q codes . k codes) * q scale * k scale on the 8-bit
- * matrix instruction; the softmax, P (bf16) and the product with V (bf16) are unchanged.  The
- * codes must have been made with block = the mask's block.  Only D = 128 with block 128, and
+ * matrix instruction; the softmax, P (bf16) and the product with V (bf16) are unchanged.
+ * code_block is the `block` the codes and scales were made with by radial_quantize_fp8; it must
+ * equal the mask's block (RADIAL_ESHAPE otherwise: the scales would be read per wrong block).  Only D = 128 with block 128, and
  * not for masks with RADIAL_MASK_TOKEN_EXACT (RADIAL_EUNSUPPORTED otherwise); other errors as
  * radial_attn_fwd.  Allocates nothing. */
 RADIAL_API int radial_quantize_fp8(int32_t B, int32_t H, int32_t N, int32_t D, radial_tensor x, int32_t block,
                                    uint8_t* codes, float* scales, void* hip_stream);
-RADIAL_API int radial_attn_fwd_fp8(int32_t B, int32_t H, int32_t N, int32_t D, const uint8_t* q_codes,
+RADIAL_API int radial_attn_fwd_fp8(int32_t B, int32_t H, int32_t N, int32_t D, int32_t code_block, const uint8_t* q_codes,
                                    const float* q_scales, const uint8_t* k_codes, const float* k_scales,
                                    radial_tensor v, radial_tensor out, float* lse, const radial_mask* mask,
                                    float scale, void* hip_stream);

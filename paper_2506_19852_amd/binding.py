@@ -77,7 +77,7 @@ def load():
     lib.radial_attn_fwd_trace_records.restype = ctypes.c_int64
     lib.radial_probe_mfma_bf16.argtypes = [ctypes.c_int64, c_void_p, ctypes.POINTER(ctypes.c_double)]
     lib.radial_quantize_fp8.argtypes = [c_int32, c_int32, c_int32, c_int32, radial_tensor, c_int32, c_void_p, c_void_p, c_void_p]
-    lib.radial_attn_fwd_fp8.argtypes = [c_int32, c_int32, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
+    lib.radial_attn_fwd_fp8.argtypes = [c_int32, c_int32, c_int32, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
                                         radial_tensor, radial_tensor, c_void_p, c_void_p, c_float, c_void_p]
     lib.radial_attn_bwd_workspace.argtypes = [c_int32, c_int32, c_int32, c_int32, c_void_p]
     lib.radial_attn_bwd_workspace.restype = c_size_t
@@ -249,17 +249,19 @@ def radial_quantize_fp8(x, block: int, codes, scales, stream=None):
                                       c_void_p(scales.data_ptr()), _stream_ptr(stream)))
 
 
-def radial_attn_fwd_fp8(q_codes, q_scales, k_codes, k_scales, v, out, lse, mask: RadialMask, scale: float, stream=None):
-    """radial_attn_fwd with the scores computed from E4M3 codes of q and k (see radial_quantize_fp8)."""
+def radial_attn_fwd_fp8(q_codes, q_scales, k_codes, k_scales, v, out, lse, mask: RadialMask, scale: float, stream=None,
+                        code_block: int = 128):
+    """radial_attn_fwd with the scores computed from E4M3 codes of q and k made by radial_quantize_fp8
+    with block = code_block."""
     import torch
     B, H, N, D = v.shape
-    nb = (N + 127) // 128
+    nb = (N + code_block - 1) // code_block
     for t, nm in ((q_codes, "q_codes"), (k_codes, "k_codes")):
         if t.dtype != torch.uint8 or not t.is_cuda or not t.is_contiguous() or tuple(t.shape) != (B, H, N, D):
             raise ValueError(f"{nm} must be a contiguous CUDA uint8 tensor [B, H, N, D]")
     for t, nm in ((q_scales, "q_scales"), (k_scales, "k_scales")):
         if t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous() or tuple(t.shape) != (B, H, nb):
-            raise ValueError(f"{nm} must be a contiguous CUDA float32 tensor [B, H, ceil(N/128)]")
+            raise ValueError(f"{nm} must be a contiguous CUDA float32 tensor [B, H, ceil(N/code_block)]")
     if tuple(out.shape) != (B, H, N, D):
         raise ValueError("out has the wrong shape")
     lse_ptr = None
@@ -267,7 +269,7 @@ def radial_attn_fwd_fp8(q_codes, q_scales, k_codes, k_scales, v, out, lse, mask:
         if lse.dtype != torch.float32 or not lse.is_cuda or not lse.is_contiguous() or tuple(lse.shape) != (B, H, N):
             raise ValueError("lse must be a contiguous CUDA float32 tensor [B, H, N]")
         lse_ptr = c_void_p(lse.data_ptr())
-    _check(load().radial_attn_fwd_fp8(B, H, N, D, c_void_p(q_codes.data_ptr()), c_void_p(q_scales.data_ptr()),
+    _check(load().radial_attn_fwd_fp8(B, H, N, D, code_block, c_void_p(q_codes.data_ptr()), c_void_p(q_scales.data_ptr()),
                                       c_void_p(k_codes.data_ptr()), c_void_p(k_scales.data_ptr()), _tensor(v, "v"),
                                       _tensor(out, "out"), lse_ptr, mask.handle, c_float(scale), _stream_ptr(stream)))
 

@@ -174,11 +174,13 @@ extern "C" int radial_quantize_fp8(int32_t B, int32_t H, int32_t N, int32_t D, r
   return launch_quantize_fp8(B, H, N, D, arg(x), block, codes, scales, (hipStream_t)hip_stream);
 }
 
-extern "C" int radial_attn_fwd_fp8(int32_t B, int32_t H, int32_t N, int32_t D, const uint8_t* q_codes, const float* q_scales,
+extern "C" int radial_attn_fwd_fp8(int32_t B, int32_t H, int32_t N, int32_t D, int32_t code_block, const uint8_t* q_codes, const float* q_scales,
                                    const uint8_t* k_codes, const float* k_scales, radial_tensor v, radial_tensor out,
                                    float* lse, const radial_mask* mask, float scale, void* hip_stream) {
   if (int rc = check_call(B, H, N, D, mask, scale)) return rc;
   if (D != 128 || mask->block != 128) return fail(RADIAL_EUNSUPPORTED, "8-bit scores need head dimension 128 and block 128");
+  if (code_block != mask->block)
+    return fail(RADIAL_ESHAPE, "codes were quantised per %d tokens, the mask's block is %d", code_block, mask->block);
   if (mask->flags & RADIAL_MASK_TOKEN_EXACT) return fail(RADIAL_EUNSUPPORTED, "8-bit scores do not apply the token rule inside blocks");
   if (!q_codes || !k_codes || !q_scales || !k_scales) return fail(RADIAL_EINVAL, "codes or scales is NULL");
   if (((uintptr_t)q_codes | (uintptr_t)k_codes) & 15u) return fail(RADIAL_ESHAPE, "codes are not 16-byte aligned");

@@ -98,6 +98,13 @@ def test_8bit_forward_refuses_what_it_does_not_support():
         rb.radial_attn_fwd_fp8(qc, qs, qc, qs, v, torch.empty_like(v), None, m, 0.1)
     assert e.value.code == -4          # RADIAL_EUNSUPPORTED
     m.free()
+    # codes quantised per 64 tokens do not fit a mask of 128-token blocks
+    m = rb.radial_mask_build(2, 128, 128, 1, 0)
+    qs64 = torch.ones((B, H, 4), dtype=torch.float32, device="cuda")
+    with pytest.raises(rb.RadialError) as e:
+        rb.radial_attn_fwd_fp8(qc, qs64, qc, qs64, v, torch.empty_like(v), None, m, 0.1, code_block=64)
+    assert e.value.code == -5          # RADIAL_ESHAPE
+    m.free()
 
 
 def test_8bit_forward_at_the_benchmark_workload_sampled_blocks():

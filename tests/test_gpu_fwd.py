@@ -198,13 +198,16 @@ def test_workload_forward(name, heads, nsample):
 
 # ---- the long end of the complexity curve --------------------------------------------------------
 
-def test_long_video_sampled_blocks():
-    """257 frames of the 720p geometry (N = 925 200, the longest point of the forward-time curve
-    that the benchmark sweeps), one head: the lists of sampled query blocks bit-exact against
-    the oracle's scan, their outputs against the oracle, radial list and all-ones list."""
+@pytest.mark.parametrize("frames,n_sample,n_dense", [(257, 10, 2), (509, 6, 1)])
+def test_long_video_sampled_blocks(frames, n_sample, n_dense):
+    """The long end of the forward-time curve at the 720p geometry, one head: 257 frames
+    (N = 925 200, the last point of the benchmark's sweep) and 509 frames (N = 1 832 400, the length
+    at which Fig. 2 of the paper quotes its attention-compute saving).  The lists of sampled query
+    blocks bit-exact against the oracle's scan, their outputs against the oracle, radial list and
+    all-ones list."""
     import dataclasses
     base = wl.WORKLOADS["cfg3_hunyuan720p"]
-    w = dataclasses.replace(base, name="hunyuan720p_f257", frames=257, H=1)
+    w = dataclasses.replace(base, name=f"hunyuan720p_f{frames}", frames=frames, H=1)
     f, s, block = w.frames, w.tokens_per_frame, w.block
     print(f"fwd long video f={f} N={w.N}", flush=True)
     x = wl.make_inputs(w, DEV)
@@ -212,21 +215,22 @@ def test_long_video_sampled_blocks():
     row_ptr, col_idx = rb.radial_mask_copy_to_host(mask)
     nb = row_ptr.size - 1
     assert nb == -(-w.N // block) and w.N % block != 0                     # ragged last block
-    qblocks = sample_qblocks(nb, np.diff(row_ptr), s, block, 10, w.seed)
+    qblocks = sample_qblocks(nb, np.diff(row_ptr), s, block, n_sample, w.seed)
     rows = []
     for qb in qblocks:
         bm, _ = obuild.mask_scan(f, s, block, 1, qb, qb + 1)
         assert np.array_equal(np.flatnonzero(bm[0]), col_idx[row_ptr[qb]:row_ptr[qb + 1]]), f"list of query block {qb}"
         rows.append(bm[0])
     out, lse = _run_fwd(x["q"], x["k"], x["v"], mask, w.scale)
-    worst = _check_blocks(out, lse, x["q"], x["k"], x["v"], rows, qblocks, block, w.scale, [(0, 0)], "257 frames radial")
-    print(f"257 frames, radial list: {len(qblocks)} query blocks (lists of {min(r.sum() for r in rows)} to "
-          f"{max(r.sum() for r in rows)} blocks), max |err| {worst:.2e}", flush=True)
+    worst = _check_blocks(out, lse, x["q"], x["k"], x["v"], rows, qblocks, block, w.scale, [(0, 0)], f"{frames} frames radial")
+    print(f"{frames} frames, radial list: {len(qblocks)} query blocks (lists of {min(r.sum() for r in rows)} to "
+          f"{max(r.sum() for r in rows)} blocks of {nb}), max |err| {worst:.2e}", flush=True)
     mask.free()
     dense = rb.radial_mask_build_dense(w.N, block)
     out, lse = _run_fwd(x["q"], x["k"], x["v"], dense, w.scale)
     ones = np.ones(nb, dtype=bool)
-    worst = _check_blocks(out, lse, x["q"], x["k"], x["v"], [ones, ones], [qblocks[1], nb - 1], block, w.scale, [(0, 0)],
-                          "257 frames dense")
-    print(f"257 frames, all-ones list: 2 query blocks, max |err| {worst:.2e}", flush=True)
+    picks = [nb - 1, qblocks[1]][:n_dense]
+    worst = _check_blocks(out, lse, x["q"], x["k"], x["v"], [ones] * len(picks), picks, block, w.scale, [(0, 0)],
+                          f"{frames} frames dense")
+    print(f"{frames} frames, all-ones list: {len(picks)} query blocks, max |err| {worst:.2e}", flush=True)
     dense.free()
