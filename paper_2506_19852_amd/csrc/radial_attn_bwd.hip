@@ -357,10 +357,11 @@ __global__ void __launch_bounds__(2 * BLK, 1) radial_bwd_dkdv_kernel(const BwdAr
   }
 }
 
-constexpr int kStageKeys = 64;  // keys per stage of the dQ kernel
-
 template <int D, int BLK>
 struct DqTile {
+  // Keys per stage of the dQ kernel.  Head dimension 128 with 64-token blocks walks half-size stages:
+  // two 64-key stage buffers (64 KiB) per 2-wave workgroup would leave a compute unit with 4 waves.
+  static constexpr int kStageKeys = (D == 128 && BLK == 64) ? 32 : 64;
   static constexpr int kWaves = BLK / 32;  // one wave per 32 query rows
   static constexpr int kThreads = 64 * kWaves;
   static constexpr int kSubs = BLK / kStageKeys;
@@ -374,7 +375,7 @@ template <int D, int BLK, bool kExact>
 __global__ void __launch_bounds__(2 * BLK, 2) radial_bwd_dq_kernel(const BwdArgs a) {
   using T = DqTile<D, BLK>;
   using SW = SwzTile<D>;
-  // [stage buffer][K, V][64 x D bf16]
+  // [stage buffer][K, V][kStageKeys x D bf16]
   __shared__ __attribute__((aligned(1024))) char lds[4 * T::kTileBytes];
   const uint32_t lds_base = lds_address(lds);
 
@@ -444,7 +445,7 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_bwd_dq_kernel(const BwdArgs
   auto issue_stage = [&](int32_t key0, int buf) {
     const uint32_t kdst = lds_base + buf * 2 * T::kTileBytes + wave * T::kLoadsPerWave * 1024;
     const uint32_t vdst = kdst + T::kTileBytes;
-    if (key0 + kStageKeys <= a.N) {
+    if (key0 + T::kStageKeys <= a.N) {
       const __bf16* kbase = kp + (int64_t)key0 * a.k.sn;  // wave-uniform
       const __bf16* vbase = vp + (int64_t)key0 * a.v.sn;
 #pragma unroll
@@ -489,19 +490,19 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_bwd_dq_kernel(const BwdArgs
         nvec = e1 + 64 + lane < n_list ? cols[e1 + 64 + lane] : 0;
         if (kExact) cvec_at = block_pos(cvec * BLK, a.rule.s);
       }
-      key0_next = __builtin_amdgcn_readlane(cvec, e1 & 63) * BLK + ((u + 1) % T::kSubs) * kStageKeys;
-      if (kExact) k_at_next = stage_pos(cvec_at, e1 & 63, ((u + 1) % T::kSubs) * kStageKeys, a.rule.s);
+      key0_next = __builtin_amdgcn_readlane(cvec, e1 & 63) * BLK + ((u + 1) % T::kSubs) * T::kStageKeys;
+      if (kExact) k_at_next = stage_pos(cvec_at, e1 & 63, ((u + 1) % T::kSubs) * T::kStageKeys, a.rule.s);
     }
     wait_all_copies();
     __syncthreads();
 
     const char* lds_k = lds + buf * 2 * T::kTileBytes;
     const char* lds_v = lds_k + T::kTileBytes;
-    const bool ragged = key0 + kStageKeys > a.N;
+    const bool ragged = key0 + T::kStageKeys > a.N;
     StageRule vis = {};
     bool skip = false;
     if (kExact) {
-      vis = stage_rule(a.rule, q_at, k_at, true);  // which of the stage's keys this lane's query sees
+      vis = stage_rule<T::kStageKeys>(a.rule, q_at, k_at, true);  // which of the stage's keys this lane's query sees
       skip = vis.none;                             // no pair of this wave's queries with the stage's keys
     }
     // The copies of a full next stage are spread over the MFMAs of the first key tile (a burst
@@ -514,7 +515,7 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_bwd_dq_kernel(const BwdArgs
       hidden = ~lane_element_bits(seen, g);
     }
     const bool any_hidden = __builtin_amdgcn_ballot_w64(hidden != 0u) != 0;
-    const bool spread = has_next && !skip && key0_next + kStageKeys <= a.N;
+    const bool spread = has_next && !skip && key0_next + T::kStageKeys <= a.N;
     if (has_next && !spread) issue_stage(key0_next, buf ^ 1);
     if (skip) {
       key0 = key0_next;
@@ -529,7 +530,7 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_bwd_dq_kernel(const BwdArgs
     const uint32_t kdst_next = lds_base + (buf ^ 1) * 2 * T::kTileBytes + wave * T::kLoadsPerWave * 1024;
     const uint32_t vdst_next = kdst_next + T::kTileBytes;
 #pragma unroll
-    for (int kt = 0; kt < kStageKeys / 32; ++kt) {
+    for (int kt = 0; kt < T::kStageKeys / 32; ++kt) {
       // S^T[key, q] and dP^T[key, q] for 32 keys x this wave's 32 queries
       f32x16 s, dp;
 #pragma unroll

@@ -12,7 +12,7 @@
 // registers, row maxima and sums are in-lane reductions plus one exchange with lane^32, and
 // the running rescale of O is a per-lane multiply.
 //
-// Key blocks are walked in stages of 64 keys.  The K and V rows of a stage are copied
+// Key blocks are walked in stages of 64 keys (32 for head dimension 128 with 64-token blocks).  The K and V rows of a stage are copied
 // HBM -> LDS by global_load_lds (no register staging) into one of two LDS stage buffers; the
 // copy of stage u+1 is issued right after the barrier that opens stage u, so it overlaps
 // the whole of stage u's arithmetic and a stage needs exactly one barrier.  The copies are
@@ -30,10 +30,11 @@
 namespace radial {
 namespace fwd {
 
-constexpr int kStageKeys = 64;  // keys per pipeline stage
-
 template <int D, int BLK>
 struct Tile {
+  // Keys per pipeline stage.  Head dimension 128 with 64-token blocks walks half-size stages: two
+  // 64-key stage buffers (64 KiB) per 2-wave workgroup would leave a compute unit with 4 waves.
+  static constexpr int kStageKeys = (D == 128 && BLK == 64) ? 32 : 64;
   static constexpr int kWaves = BLK / 32;          // one wave per 32 query rows
   static constexpr int kThreads = 64 * kWaves;
   static constexpr int kPiecesPerRow = D / 8;      // 16-byte pieces per K/V row
@@ -67,9 +68,10 @@ __device__ __forceinline__ int piece_offset(int r, int p) {
 // kTrace: also record begin, end and hardware ids of the workgroup (diagnostics build of the kernel;
 // the library's radial_attn_fwd launches kTrace = false, which carries none of it).
 template <int D, int BLK, bool kExact, bool kTrace>
+// Two waves per SIMD: two 4-wave workgroups per compute unit (BLK = 128) or four 2-wave ones (BLK = 64).
 __global__ void __launch_bounds__(2 * BLK, 2) radial_fwd_kernel(const FwdArgs a) {
   using T = Tile<D, BLK>;
-  // [stage buffer][K, V][kStageKeys x D bf16]
+  // [stage buffer][K, V][T::kStageKeys x D bf16]
   __shared__ __attribute__((aligned(1024))) char lds[2 * 2 * T::kStageBytes];
   const uint32_t lds_base = lds_address(lds);
 
@@ -155,7 +157,7 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_fwd_kernel(const FwdArgs a)
     const uint32_t vdst = kdst + T::kStageBytes;
     const __bf16* kbase = kp + (int64_t)key0 * a.k.sn;  // wave-uniform
     const __bf16* vbase = vp + (int64_t)key0 * a.v.sn;
-    if (key0 + kStageKeys <= a.N) {
+    if (key0 + T::kStageKeys <= a.N) {
 #pragma unroll
       for (int i = 0; i < T::kLoadsPerWave; ++i) copy16_to_lds_sv(kbase, koff[i], kdst + i * 1024);
 #pragma unroll
@@ -226,7 +228,7 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_fwd_kernel(const FwdArgs a)
     // ---- online softmax ------------------------------------------------------------------
     // s[kt][e] belongs to key key0 + 32kt + 8(e/4) + 4g + e%4 and query q_row.  Keys >= N do not
     // exist; under the token rule some keys are hidden from this lane's query.
-    if (key0 + kStageKeys > a.N || (kExact && vis.partial)) {
+    if (key0 + T::kStageKeys > a.N || (kExact && vis.partial)) {
       uint64_t seen = stage_prefix(a.N - key0);
       if (kExact) seen &= vis.visible_mask();
       const uint32_t hidden = ~lane_element_bits(seen, g);
@@ -308,8 +310,8 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_fwd_kernel(const FwdArgs a)
         nvec = e1 + 64 + lane < n_list ? cols[e1 + 64 + lane] : 0;
         if (kExact) cvec_at = block_pos(cvec * BLK, a.rule.s);
       }
-      key0_next = __builtin_amdgcn_readlane(cvec, e1 & 63) * BLK + ((u + 1) % T::kSubs) * kStageKeys;
-      if (kExact) k_at_next = stage_pos(cvec_at, e1 & 63, ((u + 1) % T::kSubs) * kStageKeys, a.rule.s);
+      key0_next = __builtin_amdgcn_readlane(cvec, e1 & 63) * BLK + ((u + 1) % T::kSubs) * T::kStageKeys;
+      if (kExact) k_at_next = stage_pos(cvec_at, e1 & 63, ((u + 1) % T::kSubs) * T::kStageKeys, a.rule.s);
     }
 
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's copies of stage u have landed
@@ -318,13 +320,13 @@ __global__ void __launch_bounds__(2 * BLK, 2) radial_fwd_kernel(const FwdArgs a)
     StageRule vis = {};
     bool skip = false;
     if (kExact) {
-      vis = stage_rule(a.rule, q_at, k_at, true);
+      vis = stage_rule<T::kStageKeys>(a.rule, q_at, k_at, true);
       skip = vis.none;  // nothing in this stage for any row of this wave
     }
     // The copies of stage u+1 are spread over the first product of stage u (a burst of copies
     // would hold the wave at the memory pipeline before it reaches its first MFMA); only a
     // ragged next stage, or a stage this wave skips, issues them in one go.
-    const bool spread = has_next && !skip && key0_next + kStageKeys <= a.N;
+    const bool spread = has_next && !skip && key0_next + T::kStageKeys <= a.N;
     if (has_next && !spread) issue_stage(key0_next, buf ^ 1);
     if (!skip) {
       const uint32_t on = __builtin_amdgcn_readfirstlane(spread ? ~0u : 0u);  // wave-uniform by construction

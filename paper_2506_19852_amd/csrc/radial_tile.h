@@ -144,7 +144,7 @@ __device__ __forceinline__ int32_t radial_half_width(const TokenRule& rule, int3
   return d % stride == 0 ? 0 : -1;         // sub-sampled single diagonals
 }
 
-// A stage is 64 consecutive tokens (keys for the query-stationary kernels, queries for the
+// A stage is 64 (or 32) consecutive tokens (keys for the query-stationary kernels, queries for the
 // key-stationary one) that start at (frame, pos).  With s >= 64 it touches at most the two
 // frames `frame` and `frame + 1`.
 struct StagePos {
@@ -212,6 +212,8 @@ __device__ __forceinline__ uint32_t lane_element_bits(uint64_t token_mask, int g
 }
 
 // own_is_query: the lane holds a query and the stage holds keys; otherwise the reverse.
+// kWidth: tokens in the stage (64, or 32 for the kernels that walk half-size stages).
+template <int kWidth = 64>
 __device__ __forceinline__ StageRule stage_rule(const TokenRule& rule, StagePos own, StagePos stage, bool own_is_query) {
   const int32_t s = rule.s;
   const int32_t hw0 = own_is_query ? radial_half_width(rule, own.frame, stage.frame)
@@ -220,15 +222,15 @@ __device__ __forceinline__ StageRule stage_rule(const TokenRule& rule, StagePos 
                                    : radial_half_width(rule, stage.frame + 1, own.frame);
   const int32_t split = s - stage.pos;  // stage offset at which the second frame starts
   StageRule r;
-  // first frame: positions stage.pos + x, x in [0, min(split, 64)), within hw0 of own.pos
-  const int32_t a0 = max(own.pos - hw0 - stage.pos, 0), b0 = min(own.pos + hw0 - stage.pos, min(split, 64) - 1);
+  // first frame: positions stage.pos + x, x in [0, min(split, kWidth)), within hw0 of own.pos
+  const int32_t a0 = max(own.pos - hw0 - stage.pos, 0), b0 = min(own.pos + hw0 - stage.pos, min(split, kWidth) - 1);
   r.lo0 = a0;
   r.n0 = b0 >= a0 ? (uint32_t)(b0 - a0 + 1) : 0u;
-  // second frame: positions x - split, x in [split, 64), within hw1 of own.pos
-  const int32_t a1 = max(own.pos - hw1 + split, split), b1 = min(own.pos + hw1 + split, 63);
+  // second frame: positions x - split, x in [split, kWidth), within hw1 of own.pos
+  const int32_t a1 = max(own.pos - hw1 + split, split), b1 = min(own.pos + hw1 + split, kWidth - 1);
   r.lo1 = a1;
   r.n1 = b1 >= a1 ? (uint32_t)(b1 - a1 + 1) : 0u;
-  const bool all_visible = r.n0 + r.n1 == 64u;
+  const bool all_visible = r.n0 + r.n1 == (uint32_t)kWidth;
   r.partial = __builtin_amdgcn_ballot_w64(!all_visible) != 0;
   r.none = __builtin_amdgcn_ballot_w64(r.n0 + r.n1 != 0u) == 0;
   return r;
