@@ -503,7 +503,13 @@ def main():
     if names:
         del x, out, lse, grads
         torch.cuda.empty_cache()
-        result["secondary"] = [secondary_config(nm, args, not args.no_cpu_baseline) for nm in names]
+        result["secondary"] = []
+        for nm in names:      # a failure here must not cost the headline line
+            try:
+                result["secondary"].append(secondary_config(nm, args, not args.no_cpu_baseline))
+            except Exception as e:  # noqa: BLE001
+                result["secondary"].append({"workload": nm, "error": f"{type(e).__name__}: {e}"})
+                torch.cuda.empty_cache()
     print(json.dumps(result))
 
 
