@@ -22,17 +22,19 @@ if ROOT not in sys.path:
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 
 PROFILES = os.path.join(ROOT, "profiles")
-# Sources of the attention kernels: a counter summary under profiles/ names their digest, so that a
-# summary taken on other kernel code is recognised whatever the speed of the box it was taken on.
-KERNEL_SOURCES = ("radial_attn_fwd.hip", "radial_attn_fwd_kernel.h", "radial_attn_bwd.hip", "radial_tile.h", "radial_internal.h")
+# Sources of the attention kernels: a counter summary under profiles/ names the files it depends on
+# and their digest, so that a summary taken on other kernel code is recognised whatever the speed
+# of the box it was taken on.
+FWD_KERNEL_SOURCES = ("radial_attn_fwd.hip", "radial_attn_fwd_kernel.h", "radial_tile.h", "radial_internal.h")
+BWD_KERNEL_SOURCES = FWD_KERNEL_SOURCES + ("radial_attn_bwd.hip",)
 
 
-def kernel_source_digest() -> str:
-    """First 16 hex digits of the SHA-256 over the attention kernels' source files."""
+def kernel_source_digest(names=BWD_KERNEL_SOURCES) -> str:
+    """First 16 hex digits of the SHA-256 over the named source files of the attention kernels."""
     import hashlib
     h = hashlib.sha256()
-    for name in KERNEL_SOURCES:
-        with open(os.path.join(ROOT, "paper_2506_19852_amd", "csrc", name), "rb") as f:
+    for name in names:
+        with open(os.path.join(ROOT, "paper_2506_19852_amd", "csrc", os.path.basename(name)), "rb") as f:
             h.update(f.read())
     return h.hexdigest()[:16]
 
@@ -43,7 +45,7 @@ def traffic_from_profile(workload: str, timed_kernel_ms: float, copy_bytes: floa
     (KiB per dispatch), each scaled by what the same counter read for a streaming copy of known
     size in the same run.  Returns (bytes or None, source): None when there is no summary or
     when the counters were not taken on the kernel that is running: the summary names the digest
-    of the kernel sources it was taken on, which must equal kernel_source_digest() (boxes differ
+    of the kernel source files it was taken on, which must equal their digest now (boxes differ
     by several per cent in speed, the sources do not); a summary without that line counts only
     if its kernel time is within 3 % of the one timed now."""
     import re
@@ -65,10 +67,14 @@ def traffic_from_profile(workload: str, timed_kernel_ms: float, copy_bytes: floa
     src["kernel_ms_at_capture"] = ms
     if None in (ms, fetch, write, cp_fetch, cp_write):
         return None, dict(src, note="summary lacks a figure")
-    m = re.search(r"^# kernel sources at capture[^\n]*: ([0-9a-f]{16})\s*$", text, flags=re.M)
+    m = re.search(r"^# kernel sources at capture \([^)]*, of ([\w. ]+)\): ([0-9a-f]{16})\s*$", text, flags=re.M)
     if m:
-        src["kernel_sources_at_capture"] = m.group(1)
-        if m.group(1) != kernel_source_digest():
+        src["kernel_sources_at_capture"] = m.group(2)
+        try:
+            same = m.group(2) == kernel_source_digest(m.group(1).split())
+        except OSError:
+            same = False
+        if not same:
             return None, dict(src, note="the kernel sources have changed since the capture")
         if abs(ms - timed_kernel_ms) > 0.15 * timed_kernel_ms:
             return None, dict(src, note="kernel time differs from the captured one by more than 15 %")

@@ -69,6 +69,22 @@ __global__ void __launch_bounds__(256) bwd_prepare_kernel(const BwdArgs a) {
   if (row < rows && piece == 0) a.delta[row] = sum;
 }
 
+// acc (+)= a * b with the accumulator in ordinary vector registers.  In a kernel that uses both
+// register files the compiler places every MFMA result in the accumulation file; S and dP are
+// consumed by vector instructions, which cannot read that file, so each of their 64 values per stage
+// would be copied out one register at a time (a third of the kernel's vector instructions).
+// The instruction is opaque to the compiler's hazard tracking: before a vector instruction reads
+// or writes acc the caller waits with mfma_results_settle(); a second MFMA on the same accumulator
+// may follow after one other MFMA.
+__device__ __forceinline__ void mfma32_vgpr_first(f32x16& acc, bf16x8 a, bf16x8 b) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=v"(acc) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma32_vgpr(f32x16& acc, bf16x8 a, bf16x8 b) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+// 16 wait states: more than the 11 an 8-pass MFMA needs before a vector instruction touches its result.
+__device__ __forceinline__ void mfma_results_settle() { asm volatile("s_nop 15" ::: "memory"); }
+
 // kExact (all three kernels' callers): apply the token-level rule inside the listed blocks.
 template <int D, int BLK, bool kExact>
 __global__ void __launch_bounds__(2 * BLK, 1) radial_bwd_dkdv_kernel(const BwdArgs a) {
@@ -243,8 +259,6 @@ __global__ void __launch_bounds__(2 * BLK, 1) radial_bwd_dkdv_kernel(const BwdAr
 #pragma unroll
     for (int h2 = 0; h2 < 2; ++h2) {
 #pragma unroll
-      for (int e = 0; e < 16; ++e) s[h2][e] = dp[h2][e] = 0.f;
-#pragma unroll
       for (int e4 = 0; e4 < 4; ++e4) {  // element 4*e4 + x: query row 32*h2 + 8*e4 + 4g + x of the stage
         const int ql = h2 * 32 + 8 * e4 + 4 * g;
         lse4[h2][e4] = *lds_cast<const f32x4>(st + ql * 4) * kLog2e;
@@ -284,25 +298,37 @@ __global__ void __launch_bounds__(2 * BLK, 1) radial_bwd_dkdv_kernel(const BwdAr
 #pragma unroll
     for (int t = 0; t < T::kSteps; ++t) {
       read_qg(t + kAhead);  // runs into half 1
-      s[0] = mfma32(qfr[t], kf[t], s[0]);
-      dp[0] = mfma32(gfr[t], vf[t], dp[0]);
+      if (t == 0) {
+        mfma32_vgpr_first(s[0], qfr[t], kf[t]);
+        mfma32_vgpr_first(dp[0], gfr[t], vf[t]);
+      } else {
+        mfma32_vgpr(s[0], qfr[t], kf[t]);
+        mfma32_vgpr(dp[0], gfr[t], vf[t]);
+      }
       constexpr int kCopies = 2 * T::kQLoadsPerWave + 1;
 #pragma unroll
       for (int j = t * kCopies / T::kSteps; j < (t + 1) * kCopies / T::kSteps; ++j) spread_copy(j);
       __builtin_amdgcn_sched_barrier(0);
     }
+    mfma_results_settle();
     hide(0);
     __builtin_amdgcn_sched_barrier(0);
     // ---- B: S, dP of half 1 | P, dS of half 0
 #pragma unroll
     for (int t = 0; t < T::kSteps; ++t) {
       if (t + kAhead < T::kSteps) read_qg(T::kSteps + t + kAhead);
-      s[1] = mfma32(qfr[T::kSteps + t], kf[t], s[1]);
-      dp[1] = mfma32(gfr[T::kSteps + t], vf[t], dp[1]);
+      if (t == 0) {
+        mfma32_vgpr_first(s[1], qfr[T::kSteps + t], kf[t]);
+        mfma32_vgpr_first(dp[1], gfr[T::kSteps + t], vf[t]);
+      } else {
+        mfma32_vgpr(s[1], qfr[T::kSteps + t], kf[t]);
+        mfma32_vgpr(dp[1], gfr[T::kSteps + t], vf[t]);
+      }
       if (t * 8 / T::kSteps != (t + 1) * 8 / T::kSteps) softmax_pair(0, t * 8 / T::kSteps);
       if (T::kSteps == 4) softmax_pair(0, 2 * t + 1);
       __builtin_amdgcn_sched_barrier(0);
     }
+    mfma_results_settle();
     hide(1);
     // dV^T[d, key] += dO^T[d, q] P[q, key];  dK^T[d, key] += Q^T[d, q] dS[q, key]:
     // fragment pair j = ((h2 * 2 + t2) * kDTiles + dt): transposed reads of dO and Q

@@ -26,6 +26,8 @@ def test_effective_flops_counts_real_tokens_only():
     assert bench.effective_flops(row_ptr, col_idx, n, block, d, heads) == 4 * d * pairs * heads
 
 
+NAMES = ("radial_tile.h", "radial_attn_fwd_kernel.h")  # the files a summary says it depends on
+
 SUMMARY = """{digest_line}# rocprofv3 --kernel-trace --stats -- python3 bench.py
 kernel                              calls   avg_ms    min_ms    max_ms
 radial_fwd_kernel<128, 128, false, false> radial list              4    {ms}    75.469    77.248
@@ -38,13 +40,13 @@ copy probe: WRITE_SIZE 1000000 KiB
 
 
 def write_summary(tmp_path, monkeypatch, digest, ms="76.000"):
-    line = "" if digest is None else f"# kernel sources at capture (sha256, first 16 hex digits, of a b): {digest}\n"
+    line = "" if digest is None else f"# kernel sources at capture (sha256, first 16 hex digits, of {' '.join(NAMES)}): {digest}\n"
     (tmp_path / "fwd_wl.txt").write_text(SUMMARY.format(digest_line=line, ms=ms))
     monkeypatch.setattr(bench, "PROFILES", str(tmp_path))
 
 
 def test_traffic_scaled_by_the_copy_probe(tmp_path, monkeypatch):
-    write_summary(tmp_path, monkeypatch, bench.kernel_source_digest())
+    write_summary(tmp_path, monkeypatch, bench.kernel_source_digest(NAMES))
     copy_bytes = 1000000 * 1024.0  # the copy moved 1e6 KiB each way: fetch counter read half, write counter all
     got, src = bench.traffic_from_profile("wl", 80.0, copy_bytes)  # 5 % slower box: still the same kernel
     assert got == pytest.approx((2.0e8 * 2.0 + 1.0e6 * 1.0) * 1024.0)
@@ -58,7 +60,7 @@ def test_traffic_is_null_for_other_kernel_sources(tmp_path, monkeypatch):
 
 
 def test_traffic_is_null_far_from_the_captured_time(tmp_path, monkeypatch):
-    write_summary(tmp_path, monkeypatch, bench.kernel_source_digest())
+    write_summary(tmp_path, monkeypatch, bench.kernel_source_digest(NAMES))
     assert bench.traffic_from_profile("wl", 95.0, 1e9)[0] is None
     write_summary(tmp_path, monkeypatch, None)            # a summary without digest: 3 % rule
     assert bench.traffic_from_profile("wl", 77.0, 1e9)[0] is not None
