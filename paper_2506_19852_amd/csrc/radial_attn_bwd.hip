@@ -73,17 +73,24 @@ __global__ void __launch_bounds__(256) bwd_prepare_kernel(const BwdArgs a) {
 // register files the compiler places every MFMA result in the accumulation file; S and dP are
 // consumed by vector instructions, which cannot read that file, so each of their 64 values per stage
 // would be copied out one register at a time (a third of the kernel's vector instructions).
-// The instruction is opaque to the compiler's hazard tracking: before a vector instruction reads
-// or writes acc the caller waits with mfma_results_settle(); a second MFMA on the same accumulator
-// may follow after one other MFMA.
+// The instruction is opaque to the compiler's hazard tracking.  What the compiler would guarantee
+// is arranged here or checked on the compiled code by tests/test_kernel_asm.py:
+//   - the result registers of the first k-step overlap no operand (early clobber);
+//   - no vector instruction writes an operand within two wait states before the MFMA (checked);
+//   - before a vector instruction reads or writes acc the caller waits with mfma_results_settle(),
+//     and nothing else names acc in between (checked);
+//   - a second MFMA on the same accumulator follows after one other MFMA at the earliest.
 __device__ __forceinline__ void mfma32_vgpr_first(f32x16& acc, bf16x8 a, bf16x8 b) {
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=v"(acc) : "v"(a), "v"(b));
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "v"(b));
 }
 __device__ __forceinline__ void mfma32_vgpr(f32x16& acc, bf16x8 a, bf16x8 b) {
   asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
 }
 // 16 wait states: more than the 11 an 8-pass MFMA needs before a vector instruction touches its result.
-__device__ __forceinline__ void mfma_results_settle() { asm volatile("s_nop 15" ::: "memory"); }
+// The accumulators are operands so that every later use of them stays behind the wait.
+__device__ __forceinline__ void mfma_results_settle(f32x16& acc0, f32x16& acc1) {
+  asm volatile("s_nop 15" : "+v"(acc0), "+v"(acc1));
+}
 
 // kExact (all three kernels' callers): apply the token-level rule inside the listed blocks.
 template <int D, int BLK, bool kExact>
@@ -310,7 +317,7 @@ __global__ void __launch_bounds__(2 * BLK, 1) radial_bwd_dkdv_kernel(const BwdAr
       for (int j = t * kCopies / T::kSteps; j < (t + 1) * kCopies / T::kSteps; ++j) spread_copy(j);
       __builtin_amdgcn_sched_barrier(0);
     }
-    mfma_results_settle();
+    mfma_results_settle(s[0], dp[0]);
     hide(0);
     __builtin_amdgcn_sched_barrier(0);
     // ---- B: S, dP of half 1 | P, dS of half 0
@@ -328,7 +335,7 @@ __global__ void __launch_bounds__(2 * BLK, 1) radial_bwd_dkdv_kernel(const BwdAr
       if (T::kSteps == 4) softmax_pair(0, 2 * t + 1);
       __builtin_amdgcn_sched_barrier(0);
     }
-    mfma_results_settle();
+    mfma_results_settle(s[1], dp[1]);
     hide(1);
     // dV^T[d, key] += dO^T[d, q] P[q, key];  dK^T[d, key] += Q^T[d, q] dS[q, key]:
     // fragment pair j = ((h2 * 2 + t2) * kDTiles + dt): transposed reads of dO and Q
