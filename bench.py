@@ -329,6 +329,8 @@ def main():
     ap.add_argument("--secondary", default="cfg2_wan480p,cfg4_hunyuan720p_4x,cfg5_wan480p_4x_bwd", metavar="W1,W2,...",
                     help="other workloads reported in the line's `secondary` array (kernel times only; 'none' to skip)")
     ap.add_argument("--secondary-launches", type=int, default=2)
+    ap.add_argument("--mfma-probe-seconds", type=float, default=0.0,
+                    help="after the benchmark, keep launching the MFMA-only probe for this long (for sampling board power and clock)")
     ap.add_argument("--cache-probe", action="store_true",
                     help="also run a streaming read of 2 GiB and 16 re-reads of a 64 MiB tensor (torch.neg), so that a "
                          "rocprofv3 --pmc TCC_EA0_RDREQ_sum TCC_EA0_RDREQ_LEVEL_sum run can compare the read latency seen "
@@ -486,6 +488,11 @@ def main():
     e1.record()
     torch.cuda.synchronize()
     probe_tflops = probe_flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    if args.mfma_probe_seconds > 0:   # keep the probe running so that an outside sampler can read clock and power
+        t_end = time.perf_counter() + args.mfma_probe_seconds
+        while time.perf_counter() < t_end:
+            rb.radial_probe_mfma_bf16(probe_iters)
+            torch.cuda.synchronize()
 
     achieved = fwd_flops / (kernel_ms * 1e-3) / 1e12
     traffic, traffic_source = None, None
